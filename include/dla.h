@@ -1,0 +1,182 @@
+/*
+ * dla.h - C ABI of the MI355X (gfx950) dense linear-algebra kernels that the
+ * paper's autotuner compiles and times: 3mm, LU without pivoting, Cholesky
+ * (paper, Section "Linear Algebra Benchmarks").
+ *
+ * Conventions that hold for every entry point
+ *   - Matrices are ROW-MAJOR (the paper's X[i, j] indexing in the 3mm
+ *     tensor-expression listing); a leading dimension is counted in elements
+ *     and must be >= the number of columns.
+ *   - Every pointer whose name starts with d_ is a DEVICE pointer owned by the
+ *     caller.  The library never allocates or frees caller-visible memory and
+ *     keeps no pointer after the call returns.  Scratch memory comes in
+ *     through an explicit workspace argument whose size the matching
+ *     *_workspace_bytes() query returns.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it asynchronously; no entry point synchronises
+ *     the device.  With lookahead enabled a factorisation also uses one
+ *     library-owned helper stream that is fork/joined to hip_stream with
+ *     events, so from the caller's side the call still behaves as one piece of
+ *     work on hip_stream.
+ *   - Return value: DLA_SUCCESS (0); -i when the i-th argument (1-based) is
+ *     invalid (null pointer, negative size, leading dimension too small,
+ *     unknown dtype, misaligned pointer); or one of the positive DLA_ERR_*
+ *     codes.  Argument errors are detected before any GPU work is enqueued.
+ *   - Tile sizes, block sizes and unroll factors are explicit parameters (the
+ *     paper's split factors P0..P5 of the 3mm code mold and the two tile
+ *     parameters of LU/Cholesky) so that a search can drive them.  Only
+ *     combinations from a pre-instantiated menu are legal; anything else
+ *     returns DLA_ERR_UNSUPPORTED_PARAMS instead of running a slow path.
+ *     Tiles need not divide the matrix dimensions.
+ */
+#ifndef DLA_H
+#define DLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DLA_F64 = 0, DLA_F32 = 1 } dla_dtype;
+
+enum {
+  DLA_SUCCESS = 0,
+  DLA_ERR_UNSUPPORTED_PARAMS = 1, /* tile/block combination not in the menu          */
+  DLA_ERR_WORKSPACE = 2,          /* workspace missing, misaligned or too small        */
+  DLA_ERR_HIP = 3,                /* a HIP call or kernel launch failed                */
+  DLA_ERR_TOO_LARGE = 4           /* a dimension exceeds what the kernels index (2^31) */
+};
+
+/* Kernel selectors for dla_default_params(). */
+enum { DLA_KERNEL_MM3 = 0, DLA_KERNEL_LU = 1, DLA_KERNEL_CHOLESKY = 2 };
+
+/*
+ * Schedule of one GEMM.  tile_m x tile_n is the macro-tile one workgroup
+ * computes: the paper's split factors of the y and x axes of one 3mm product
+ * (code mold, parameters P0..P5).  The remaining fields are the extra knobs of
+ * the native kernel.  A field set to 0 means "library default for this
+ * macro-tile".
+ */
+typedef struct {
+  int tile_m, tile_n; /* workgroup macro-tile, multiples of 16                                 */
+  int tile_k;         /* depth of the k-slab staged in LDS per main-loop iteration (8/16/32)    */
+  int unroll_k;       /* 16x16x4 MFMA k-steps unrolled together inside a slab (1, 2, 4, 8)      */
+  int wave_m, wave_n; /* sub-tile one 64-lane wavefront accumulates in registers                */
+} dla_gemm_params;
+
+/*
+ * Schedule of a blocked right-looking factorisation.  nb is the panel width
+ * (block size), update the schedule of the trailing-matrix (Schur complement)
+ * GEMM that dominates the run time.
+ */
+typedef struct {
+  int nb;        /* block size, multiple of 16, 16..128 (0 = default)                          */
+  int lookahead; /* 0: one stream, strictly sequential steps; 1: factor panel k+1 on a helper
+                    stream while the rest of update k runs; -1 = default                       */
+  dla_gemm_params update;
+} dla_factor_params;
+
+/* The six tile parameters of the 3mm code mold: (P0,P1) -> e, (P2,P3) -> f, (P4,P5) -> g. */
+typedef struct {
+  dla_gemm_params e, f, g;
+} dla_mm3_params;
+
+/*
+ * LU decomposition without pivoting, A = L*U, in place (paper, Section
+ * "Linear Algebra Benchmarks": L lower, U upper, no pivoting).
+ *   d_a        device, n x n, row-major with leading dimension lda; on exit the
+ *              strict lower triangle holds L (unit diagonal not stored) and the
+ *              upper triangle including the diagonal holds U.
+ *   p          schedule, or NULL for defaults.
+ *   d_workspace / workspace_bytes   device scratch of at least
+ *              factor_workspace_bytes(n, dt, p) bytes, 256-byte aligned.
+ *   d_info     device int, may be NULL.  Written asynchronously: 0, or the
+ *              1-based index of the first exactly-zero pivot, after which the
+ *              content of A is unspecified (the call itself still completes).
+ * n == 0 is a successful no-op.
+ */
+int lu_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p,
+              void* d_workspace, size_t workspace_bytes, void* hip_stream, int* d_info);
+
+/*
+ * Cholesky decomposition A = L*L^T, in place (same Section).  Only the lower
+ * triangle of A (diagonal included) is read.  On exit the lower triangle holds
+ * L and the strict upper triangle is zero.  d_info: 0, or the 1-based index of
+ * the first pivot that is not strictly positive.  Other arguments as lu_factor.
+ */
+int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream, int* d_info);
+
+/* Scratch bytes lu_factor / cholesky_factor need (same for both). 0 on invalid arguments. */
+size_t factor_workspace_bytes(int64_t n, dla_dtype dt, const dla_factor_params* p);
+
+/*
+ * 3mm: G = (A*B)*(C*D) (paper, Section "Linear Algebra Benchmarks" and the
+ * 3mm_basic listing: E = A*B and F = C*D are internal temporaries, the
+ * arguments are A, B, C, D and G).
+ *   A ni x nk, B nk x nj, C nj x nm, D nm x nl, G ni x nl; A..D are read only,
+ *   G is overwritten.  E (ni x nj) and F (nj x nl) live in the workspace
+ *   (mm3_workspace_bytes), rounded to the element type between products as in
+ *   the listing.  E and F are computed by one grouped launch, G by a second.
+ * Any dimension equal to 0 yields an empty or all-zero G and succeeds.
+ */
+int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc,
+        const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj,
+        int64_t nm, int64_t nl, dla_dtype dt, const dla_mm3_params* p, void* d_workspace,
+        size_t workspace_bytes, void* hip_stream);
+
+size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt);
+
+/*
+ * The GEMM building block of all three kernels, exported so that a search can
+ * time one schedule in isolation.
+ *   op 0:  C  = A*B            A m x k, B k x n
+ *   op 1:  C -= A*B            (the LU trailing update)
+ *   op 2:  lower(C) -= A*B^T   A m x k, B n x k, m == n; tiles that lie strictly
+ *          above the diagonal are skipped, the upper part of diagonal tiles
+ *          is computed too (the Cholesky trailing update)
+ * C must not overlap A or B.
+ */
+int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c,
+             int64_t ldc, int64_t m, int64_t n, int64_t k, dla_dtype dt, const dla_gemm_params* p,
+             void* hip_stream);
+
+/* 1 if the schedule is in the menu for dt (fields equal to 0 are filled with defaults first), else 0. */
+int dla_gemm_params_supported(dla_dtype dt, const dla_gemm_params* p);
+
+/*
+ * Writes up to cap legal schedules to out (may be NULL when cap == 0) and
+ * returns how many the menu holds: a search builds its space from this.
+ */
+int dla_enumerate_tiles(dla_dtype dt, dla_gemm_params* out, int cap);
+
+/* 1 if nb is a legal block size for the factorisations, else 0. */
+int dla_block_size_supported(dla_dtype dt, int nb);
+
+/*
+ * Fills *out with the default schedule for a kernel (DLA_KERNEL_*) at size n:
+ * out points to a dla_mm3_params for DLA_KERNEL_MM3, else to a dla_factor_params.
+ */
+int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out);
+
+/*
+ * Optional per-phase timing for benchmarks.  While enabled, the factorisations
+ * and mm3 bracket every launch of the named phase with events on the stream
+ * the kernel runs on.  dla_profile_read synchronises those events and returns
+ * accumulated milliseconds and launch counts, then clears them.
+ * Phases: 0 = GEMM (trailing update / 3mm products), 1 = diagonal block, 2 = TRSM.
+ * Profiling is per process, not thread safe, and perturbs the pipeline; leave
+ * it off when timing whole calls.
+ */
+int dla_profile_enable(int on);
+int dla_profile_read(int phase, double* ms_total, int64_t* launches, double* flops);
+
+const char* dla_strerror(int code);
+const char* dla_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLA_H */

@@ -1,0 +1,406 @@
+// C-ABI entry points (see include/dla.h): argument validation, schedule
+// resolution, 3mm driver, GEMM export, profiler.  Argument errors are reported
+// before any HIP call so they can be exercised on a machine without a GPU.
+#include <mutex>
+#include <vector>
+#include "host_common.hpp"
+
+namespace dla {
+
+// ------------------------------------------------------------------ schedule menu
+struct TileEntry {
+  int tm, tn, wm, wn;
+};
+static const TileEntry kTiles[] = {
+#define DLA_ROW(TM, TN, WM, WN) {TM, TN, WM, WN},
+    DLA_TILE_MENU(DLA_ROW)
+#undef DLA_ROW
+};
+struct KuEntry {
+  int tk, uk;
+};
+static const KuEntry kKu[] = {
+#define DLA_ROW(TK, UK) {TK, UK},
+    DLA_KU_MENU(DLA_ROW)
+#undef DLA_ROW
+};
+static const int kNumTiles = (int)(sizeof(kTiles) / sizeof(kTiles[0]));
+static const int kNumKu = (int)(sizeof(kKu) / sizeof(kKu[0]));
+
+static int esize(dla_dtype dt) { return dt == DLA_F64 ? 8 : 4; }
+
+int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out) {
+  GemmSchedule s = {0, 0, 0, 0, 0, 0};
+  if (in) s = GemmSchedule{in->tile_m, in->tile_n, in->tile_k, in->unroll_k, in->wave_m, in->wave_n};
+  if (s.tm < 0 || s.tn < 0 || s.tk < 0 || s.uk < 0 || s.wm < 0 || s.wn < 0) return DLA_ERR_UNSUPPORTED_PARAMS;
+  if (s.tm == 0 && s.tn == 0) s.tm = s.tn = 128;
+  if (s.tm == 0) s.tm = s.tn;
+  if (s.tn == 0) s.tn = s.tm;
+  if (s.wm == 0 || s.wn == 0) {  // default wave split: first menu row with this macro-tile
+    bool found = false;
+    for (int i = 0; i < kNumTiles && !found; ++i)
+      if (kTiles[i].tm == s.tm && kTiles[i].tn == s.tn && (s.wm == 0 || s.wm == kTiles[i].wm) &&
+          (s.wn == 0 || s.wn == kTiles[i].wn)) {
+        s.wm = kTiles[i].wm;
+        s.wn = kTiles[i].wn;
+        found = true;
+      }
+    if (!found) return DLA_ERR_UNSUPPORTED_PARAMS;
+  }
+  if (s.tk == 0) s.tk = 16;
+  if (s.uk == 0) {  // largest unroll instantiated for this slab depth
+    for (int i = 0; i < kNumKu; ++i)
+      if (kKu[i].tk == s.tk && kKu[i].uk > s.uk) s.uk = kKu[i].uk;
+    if (s.uk == 0) return DLA_ERR_UNSUPPORTED_PARAMS;
+  }
+  bool tile_ok = false, ku_ok = false;
+  for (int i = 0; i < kNumTiles; ++i)
+    tile_ok |= (kTiles[i].tm == s.tm && kTiles[i].tn == s.tn && kTiles[i].wm == s.wm && kTiles[i].wn == s.wn);
+  for (int i = 0; i < kNumKu; ++i) ku_ok |= (kKu[i].tk == s.tk && kKu[i].uk == s.uk);
+  if (!tile_ok || !ku_ok) return DLA_ERR_UNSUPPORTED_PARAMS;
+  if (op == OP_SUB_NT_LOWER && s.tm != s.tn) return DLA_ERR_UNSUPPORTED_PARAMS;
+  if (gemm_lds_bytes(s, op == OP_SUB_NT_LOWER, esize(dt)) > kMaxLdsBytes) return DLA_ERR_UNSUPPORTED_PARAMS;
+  *out = s;
+  return DLA_SUCCESS;
+}
+
+// ------------------------------------------------------------------ profiler
+struct ProfileRecord {
+  hipEvent_t e0, e1;
+  int phase;
+  double flops;
+};
+static bool g_profile_on = false;
+static std::vector<ProfileRecord> g_records;
+static std::vector<hipEvent_t> g_event_pool;
+static std::mutex g_profile_mutex;
+
+static hipEvent_t take_event() {
+  if (!g_event_pool.empty()) {
+    hipEvent_t e = g_event_pool.back();
+    g_event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+int profile_begin(int phase, double flops, hipStream_t st) {
+  if (!g_profile_on) return -1;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  ProfileRecord r;
+  r.e0 = take_event();
+  r.e1 = take_event();
+  r.phase = phase;
+  r.flops = flops;
+  if (!r.e0 || !r.e1) return -1;
+  (void)hipEventRecord(r.e0, st);
+  g_records.push_back(r);
+  return (int)g_records.size() - 1;
+}
+
+void profile_end(int slot, hipStream_t st) {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  if (slot < (int)g_records.size()) (void)hipEventRecord(g_records[slot].e1, st);
+}
+
+// ------------------------------------------------------------------ GEMM wrapper
+template <typename T>
+int run_gemm(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B, int64_t ldb, T* C, int64_t ldc,
+             int64_t M, int64_t N, int64_t K, hipStream_t st) {
+  if (M <= 0 || N <= 0) return DLA_SUCCESS;
+  GemmGroup<T> g;
+  g.nprob = 1;
+  g.prob[0] = make_problem<T>(s, op, A, lda, B, ldb, C, ldc, M, N, K, 0);
+  g.prob[1] = g.prob[0];
+  g.total_tiles = problem_tiles(s, op, g.prob[0]);
+  const double flops = (op == OP_SUB_NT_LOWER ? 1.0 : 2.0) * (double)M * (double)N * (double)K;
+  ProfileScope scope(PHASE_GEMM, flops, st);
+  return launch_gemm<T>(s, op, g, st);
+}
+template int run_gemm<double>(const GemmSchedule&, int, const double*, int64_t, const double*, int64_t, double*,
+                              int64_t, int64_t, int64_t, int64_t, hipStream_t);
+template int run_gemm<float>(const GemmSchedule&, int, const float*, int64_t, const float*, int64_t, float*, int64_t,
+                             int64_t, int64_t, int64_t, hipStream_t);
+
+// C = 0 for the degenerate k == 0 product.
+template <typename T>
+__global__ void fill_zero_kernel(T* c, int64_t ld, int rows, int cols) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)rows * cols) c[(i / cols) * ld + (i % cols)] = T(0);
+}
+template <typename T>
+static int fill_zero(T* c, int64_t ld, int64_t rows, int64_t cols, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return DLA_SUCCESS;
+  const int64_t total = rows * cols;
+  hipLaunchKernelGGL(fill_zero_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, c, ld, (int)rows,
+                     (int)cols);
+  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+}
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Mm3Layout {
+  int64_t lde, ldf;
+  size_t e_bytes, f_bytes;
+};
+static Mm3Layout mm3_layout(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt) {
+  Mm3Layout L;
+  const size_t es = (size_t)esize(dt);
+  L.lde = (int64_t)round_up((size_t)(nj > 0 ? nj : 1), 16);  // rows start on 64/128-byte boundaries
+  L.ldf = (int64_t)round_up((size_t)(nl > 0 ? nl : 1), 16);
+  L.e_bytes = round_up((size_t)(ni > 0 ? ni : 0) * (size_t)L.lde * es, 256);
+  L.f_bytes = round_up((size_t)(nj > 0 ? nj : 0) * (size_t)L.ldf * es, 256);
+  return L;
+}
+
+template <typename T>
+static int mm3_impl(const T* A, int64_t lda, const T* B, int64_t ldb, const T* C, int64_t ldc, const T* D,
+                    int64_t ldd, T* G, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm, int64_t nl,
+                    const GemmSchedule& se, const GemmSchedule& sf, const GemmSchedule& sg, void* ws,
+                    hipStream_t st) {
+  const Mm3Layout L = mm3_layout(ni, nj, nl, sizeof(T) == 8 ? DLA_F64 : DLA_F32);
+  T* E = reinterpret_cast<T*>(ws);
+  T* F = reinterpret_cast<T*>(reinterpret_cast<unsigned char*>(ws) + L.e_bytes);
+  if (ni == 0 || nl == 0) return DLA_SUCCESS;  // G is empty
+  int rc;
+  if (nj == 0) return fill_zero(G, ldg, ni, nl, st);  // E and F are empty: G = 0
+  // E = A*B and F = C*D are independent: one grouped launch when their schedules coincide.
+  const bool same = se.tm == sf.tm && se.tn == sf.tn && se.tk == sf.tk && se.uk == sf.uk && se.wm == sf.wm &&
+                    se.wn == sf.wn;
+  if (nk == 0) { if ((rc = fill_zero(E, L.lde, ni, nj, st)) != DLA_SUCCESS) return rc; }
+  if (nm == 0) { if ((rc = fill_zero(F, L.ldf, nj, nl, st)) != DLA_SUCCESS) return rc; }
+  if (same && nk > 0 && nm > 0) {
+    GemmGroup<T> g;
+    g.nprob = 2;
+    g.prob[0] = make_problem<T>(se, OP_ASSIGN, A, lda, B, ldb, E, L.lde, ni, nj, nk, 0);
+    const int t0 = problem_tiles(se, OP_ASSIGN, g.prob[0]);
+    g.prob[1] = make_problem<T>(se, OP_ASSIGN, C, ldc, D, ldd, F, L.ldf, nj, nl, nm, t0);
+    g.total_tiles = t0 + problem_tiles(se, OP_ASSIGN, g.prob[1]);
+    ProfileScope scope(PHASE_GEMM, 2.0 * ((double)ni * nj * nk + (double)nj * nl * nm), st);
+    if ((rc = launch_gemm<T>(se, OP_ASSIGN, g, st)) != DLA_SUCCESS) return rc;
+  } else {
+    if (nk > 0 && (rc = run_gemm<T>(se, OP_ASSIGN, A, lda, B, ldb, E, L.lde, ni, nj, nk, st)) != DLA_SUCCESS) return rc;
+    if (nm > 0 && (rc = run_gemm<T>(sf, OP_ASSIGN, C, ldc, D, ldd, F, L.ldf, nj, nl, nm, st)) != DLA_SUCCESS) return rc;
+  }
+  return run_gemm<T>(sg, OP_ASSIGN, E, L.lde, F, L.ldf, G, ldg, ni, nl, nj, st);
+}
+
+static const int64_t kMaxDim = (int64_t)1 << 30;
+
+}  // namespace dla
+
+using namespace dla;
+
+extern "C" {
+
+const char* dla_version(void) { return "dla-mi355x 0.1 (gfx950, MFMA 16x16x4)"; }
+
+const char* dla_strerror(int code) {
+  switch (code) {
+    case DLA_SUCCESS: return "success";
+    case DLA_ERR_UNSUPPORTED_PARAMS: return "tile/block parameters are not in the pre-instantiated menu";
+    case DLA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DLA_ERR_HIP: return "a HIP call or kernel launch failed";
+    case DLA_ERR_TOO_LARGE: return "dimension too large";
+    default: return code < 0 ? "invalid argument (its 1-based position is the negated code)" : "unknown error code";
+  }
+}
+
+int dla_gemm_params_supported(dla_dtype dt, const dla_gemm_params* p) {
+  if (dt != DLA_F64 && dt != DLA_F32) return 0;
+  GemmSchedule s;
+  return resolve_schedule(dt, p, OP_ASSIGN, &s) == DLA_SUCCESS ? 1 : 0;
+}
+
+int dla_enumerate_tiles(dla_dtype dt, dla_gemm_params* out, int cap) {
+  if (dt != DLA_F64 && dt != DLA_F32) return 0;
+  int count = 0;
+  for (int i = 0; i < kNumTiles; ++i)
+    for (int j = 0; j < kNumKu; ++j) {
+      GemmSchedule s = {kTiles[i].tm, kTiles[i].tn, kKu[j].tk, kKu[j].uk, kTiles[i].wm, kTiles[i].wn};
+      if (gemm_lds_bytes(s, false, esize(dt)) > kMaxLdsBytes) continue;
+      if (out && count < cap) out[count] = dla_gemm_params{s.tm, s.tn, s.tk, s.uk, s.wm, s.wn};
+      ++count;
+    }
+  return count;
+}
+
+int dla_block_size_supported(dla_dtype dt, int nb) {
+  if (dt != DLA_F64 && dt != DLA_F32) return 0;
+  return (nb >= 16 && nb <= 128 && nb % 16 == 0) ? 1 : 0;
+}
+
+int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
+  if (kernel < DLA_KERNEL_MM3 || kernel > DLA_KERNEL_CHOLESKY) return -1;
+  if (n < 0) return -2;
+  if (dt != DLA_F64 && dt != DLA_F32) return -3;
+  if (!out) return -4;
+  if (kernel == DLA_KERNEL_MM3) {
+    dla_mm3_params* p = static_cast<dla_mm3_params*>(out);
+    GemmSchedule s;
+    resolve_schedule(dt, nullptr, OP_ASSIGN, &s);
+    const dla_gemm_params gp = {s.tm, s.tn, s.tk, s.uk, s.wm, s.wn};
+    p->e = p->f = p->g = gp;
+    return DLA_SUCCESS;
+  }
+  dla_factor_params* p = static_cast<dla_factor_params*>(out);
+  int nb, la;
+  GemmSchedule s;
+  const int op = kernel == DLA_KERNEL_LU ? OP_SUB : OP_SUB_NT_LOWER;
+  int rc = resolve_factor_params(dt, n, nullptr, op, &nb, &la, &s);
+  if (rc != DLA_SUCCESS) return rc;
+  p->nb = nb;
+  p->lookahead = la;
+  p->update = dla_gemm_params{s.tm, s.tn, s.tk, s.uk, s.wm, s.wn};
+  return DLA_SUCCESS;
+}
+
+int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c, int64_t ldc, int64_t m,
+             int64_t n, int64_t k, dla_dtype dt, const dla_gemm_params* p, void* hip_stream) {
+  if (op < OP_ASSIGN || op > OP_SUB_NT_LOWER) return -1;
+  if (m < 0) return -8;
+  if (n < 0) return -9;
+  if (k < 0) return -10;
+  if (dt != DLA_F64 && dt != DLA_F32) return -11;
+  if (op == OP_SUB_NT_LOWER && m != n) return -9;
+  if (m > kMaxDim || n > kMaxDim || k > kMaxDim) return DLA_ERR_TOO_LARGE;
+  const bool empty = (m == 0 || n == 0);
+  if (!empty && k > 0 && !d_a) return -2;
+  if (!empty && k > 0 && !d_b) return -4;
+  if (!empty && !d_c) return -6;
+  if (lda < (k > 0 ? k : 1)) return -3;
+  if (ldb < (op == OP_SUB_NT_LOWER ? (k > 0 ? k : 1) : (n > 0 ? n : 1))) return -5;
+  if (ldc < (n > 0 ? n : 1)) return -7;
+  const size_t es = (size_t)esize(dt);
+  if (((uintptr_t)d_a % es) || ((uintptr_t)d_b % es)) return -2;
+  if ((uintptr_t)d_c % es) return -6;
+  GemmSchedule s;
+  int rc = resolve_schedule(dt, p, op, &s);
+  if (rc != DLA_SUCCESS) return rc;
+  if (empty) return DLA_SUCCESS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (k == 0) {
+    if (op != OP_ASSIGN) return DLA_SUCCESS;
+    return dt == DLA_F64 ? fill_zero((double*)d_c, ldc, m, n, st) : fill_zero((float*)d_c, ldc, m, n, st);
+  }
+  if (dt == DLA_F64)
+    return run_gemm<double>(s, op, (const double*)d_a, lda, (const double*)d_b, ldb, (double*)d_c, ldc, m, n, k, st);
+  return run_gemm<float>(s, op, (const float*)d_a, lda, (const float*)d_b, ldb, (float*)d_c, ldc, m, n, k, st);
+}
+
+size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt) {
+  if (ni < 0 || nj < 0 || nl < 0 || (dt != DLA_F64 && dt != DLA_F32)) return 0;
+  if (ni > kMaxDim || nj > kMaxDim || nl > kMaxDim) return 0;
+  const Mm3Layout L = mm3_layout(ni, nj, nl, dt);
+  return L.e_bytes + L.f_bytes + 256;
+}
+
+int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc, const void* d_d,
+        int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm, int64_t nl,
+        dla_dtype dt, const dla_mm3_params* p, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (ni < 0) return -11;
+  if (nk < 0) return -12;
+  if (nj < 0) return -13;
+  if (nm < 0) return -14;
+  if (nl < 0) return -15;
+  if (dt != DLA_F64 && dt != DLA_F32) return -16;
+  if (ni > kMaxDim || nk > kMaxDim || nj > kMaxDim || nm > kMaxDim || nl > kMaxDim) return DLA_ERR_TOO_LARGE;
+  const size_t es = (size_t)esize(dt);
+  if (ni > 0 && nk > 0 && (!d_a || (uintptr_t)d_a % es)) return -1;
+  if (lda < (nk > 0 ? nk : 1)) return -2;
+  if (nk > 0 && nj > 0 && (!d_b || (uintptr_t)d_b % es)) return -3;
+  if (ldb < (nj > 0 ? nj : 1)) return -4;
+  if (nj > 0 && nm > 0 && (!d_c || (uintptr_t)d_c % es)) return -5;
+  if (ldc < (nm > 0 ? nm : 1)) return -6;
+  if (nm > 0 && nl > 0 && (!d_d || (uintptr_t)d_d % es)) return -7;
+  if (ldd < (nl > 0 ? nl : 1)) return -8;
+  if (ni > 0 && nl > 0 && (!d_g || (uintptr_t)d_g % es)) return -9;
+  if (ldg < (nl > 0 ? nl : 1)) return -10;
+  GemmSchedule se, sf, sg;
+  int rc;
+  if ((rc = resolve_schedule(dt, p ? &p->e : nullptr, OP_ASSIGN, &se)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->f : nullptr, OP_ASSIGN, &sf)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->g : nullptr, OP_ASSIGN, &sg)) != DLA_SUCCESS) return rc;
+  const size_t need = mm3_workspace_bytes(ni, nj, nl, dt);
+  const bool uses_ws = (ni > 0 && nl > 0 && nj > 0);
+  if (uses_ws && (!d_workspace || workspace_bytes < need || (uintptr_t)d_workspace % 256)) return DLA_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return mm3_impl<double>((const double*)d_a, lda, (const double*)d_b, ldb, (const double*)d_c, ldc,
+                            (const double*)d_d, ldd, (double*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, d_workspace,
+                            st);
+  return mm3_impl<float>((const float*)d_a, lda, (const float*)d_b, ldb, (const float*)d_c, ldc, (const float*)d_d,
+                         ldd, (float*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, d_workspace, st);
+}
+
+static int factor_common_checks(void* d_a, int64_t n, int64_t lda, dla_dtype dt) {
+  if (n < 0) return -2;
+  if (dt != DLA_F64 && dt != DLA_F32) return -4;
+  if (n > 0 && !d_a) return -1;
+  if (n > 0 && ((uintptr_t)d_a % (size_t)esize(dt))) return -1;
+  if (lda < (n > 0 ? n : 1)) return -3;
+  if (n > kMaxDim) return DLA_ERR_TOO_LARGE;
+  return DLA_SUCCESS;
+}
+
+size_t factor_workspace_bytes(int64_t n, dla_dtype dt, const dla_factor_params* p) {
+  if (n < 0 || n > kMaxDim || (dt != DLA_F64 && dt != DLA_F32)) return 0;
+  return factor_workspace_bytes_impl(n, dt, p);
+}
+
+int lu_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p, void* d_workspace,
+              size_t workspace_bytes, void* hip_stream, int* d_info) {
+  int rc = factor_common_checks(d_a, n, lda, dt);
+  if (rc != DLA_SUCCESS) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64) return lu_factor_impl<double>((double*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
+  return lu_factor_impl<float>((float*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
+}
+
+int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p, void* d_workspace,
+                    size_t workspace_bytes, void* hip_stream, int* d_info) {
+  int rc = factor_common_checks(d_a, n, lda, dt);
+  if (rc != DLA_SUCCESS) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return cholesky_factor_impl<double>((double*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
+  return cholesky_factor_impl<float>((float*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
+}
+
+int dla_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  g_profile_on = (on != 0);
+  return DLA_SUCCESS;
+}
+
+int dla_profile_read(int phase, double* ms_total, int64_t* launches, double* flops) {
+  if (phase < 0 || phase >= PHASE_COUNT) return -1;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  double ms = 0.0, fl = 0.0;
+  int64_t cnt = 0;
+  std::vector<ProfileRecord> keep;
+  for (const ProfileRecord& r : g_records) {
+    if (r.phase != phase) {
+      keep.push_back(r);
+      continue;
+    }
+    float t = 0.f;
+    if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&t, r.e0, r.e1) == hipSuccess) {
+      ms += t;
+      fl += r.flops;
+      ++cnt;
+    }
+    g_event_pool.push_back(r.e0);
+    g_event_pool.push_back(r.e1);
+  }
+  g_records.swap(keep);
+  if (ms_total) *ms_total = ms;
+  if (launches) *launches = cnt;
+  if (flops) *flops = fl;
+  return DLA_SUCCESS;
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Shared device-side definitions of the HIP kernels: MFMA wrappers and the
+// register layouts of the 16x16x4 matrix instructions on gfx950.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dla {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef double double2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// One 16x16x4 MFMA step  D(16x16) = A(16x4) * B(4x16) + C  on a 64-lane wavefront.
+// Operand layouts (checked against the hardware with a register-dump probe):
+//   A: lane l holds A[l % 16][l / 16]          B: lane l holds B[l / 16][l % 16]
+//   D, fp64: register v of lane l holds D[4*v + l/16][l % 16]
+//   D, fp32: register v of lane l holds D[4*(l/16) + v][l % 16]
+// The fp64 D layout is the B layout of k-step v, so a result block can be fed
+// back as the right-hand operand of a following product without a shuffle.
+template <typename T>
+struct Mfma;
+
+template <>
+struct Mfma<double> {
+  using acc_t = double4_t;
+  using vec2_t = double2_t;
+  __device__ static inline acc_t mma(double a, double b, acc_t c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+  }
+  __device__ static inline int row_of(int v, int lane) { return 4 * v + (lane >> 4); }
+};
+
+template <>
+struct Mfma<float> {
+  using acc_t = float4_t;
+  using vec2_t = float2_t;
+  __device__ static inline acc_t mma(float a, float b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  __device__ static inline int row_of(int v, int lane) { return 4 * (lane >> 4) + v; }
+};
+
+constexpr int kNumXcd = 8;  // MI355X: 8 accelerator complex dies, workgroups are dealt round-robin
+
+// Workgroup id -> logical work item so that each XCD (and its private L2)
+// walks one contiguous range of the work list.
+__device__ inline int xcd_contiguous_id(int bid, int total) {
+  const int q = total / kNumXcd, r = total % kNumXcd;
+  const int x = bid % kNumXcd, t = bid / kNumXcd;
+  return x * q + (x < r ? x : r) + t;
+}
+
+}  // namespace dla

@@ -1,0 +1,69 @@
+// Host-side helpers shared by the C-ABI entry points: schedule resolution,
+// GEMM problem descriptors and the optional per-phase event profiler.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "dla_codes.hpp"
+#include "gemm_dispatch.hpp"
+
+namespace dla {
+
+enum Phase { PHASE_GEMM = 0, PHASE_DIAG = 1, PHASE_TRSM = 2, PHASE_COUNT = 3 };
+
+// Fills defaults into a user schedule and checks it against the menu.
+// op selects which LDS layout the fit check uses.
+int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out);
+
+template <typename T>
+inline GemmProblem<T> make_problem(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B, int64_t ldb,
+                                   T* C, int64_t ldc, int64_t M, int64_t N, int64_t K, int tile_begin) {
+  GemmProblem<T> p;
+  p.A = A;
+  p.B = B;
+  p.C = C;
+  p.lda = lda;
+  p.ldb = ldb;
+  p.ldc = ldc;
+  p.M = (int)M;
+  p.N = (int)N;
+  p.K = (int)K;
+  p.tiles_m = (int)((M + s.tm - 1) / s.tm);
+  p.tiles_n = (int)((N + s.tn - 1) / s.tn);
+  p.tile_begin = tile_begin;
+  return p;
+}
+
+template <typename T>
+inline int problem_tiles(const GemmSchedule& s, int op, const GemmProblem<T>& p) {
+  if (op == OP_SUB_NT_LOWER && s.tm == s.tn) return p.tiles_m * (p.tiles_m + 1) / 2;
+  return p.tiles_m * p.tiles_n;
+}
+
+// One GEMM on a stream (C op= A*B), with profiling brackets when enabled.
+template <typename T>
+int run_gemm(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B, int64_t ldb, T* C, int64_t ldc,
+             int64_t M, int64_t N, int64_t K, hipStream_t st);
+
+// Profiler brackets: begin returns a slot (or -1 when profiling is off).
+int profile_begin(int phase, double flops, hipStream_t st);
+void profile_end(int slot, hipStream_t st);
+
+struct ProfileScope {
+  int slot;
+  hipStream_t st;
+  ProfileScope(int phase, double flops, hipStream_t s) : slot(profile_begin(phase, flops, s)), st(s) {}
+  ~ProfileScope() { profile_end(slot, st); }
+};
+
+// Factorisation drivers (factor.hip).
+template <typename T>
+int lu_factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
+                   hipStream_t st, int* d_info);
+template <typename T>
+int cholesky_factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
+                         hipStream_t st, int* d_info);
+size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p);
+int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
+                          GemmSchedule* upd);
+
+}  // namespace dla

@@ -1,0 +1,140 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the public header declares, the schedule menu answers queries,
+and argument errors are reported before any GPU work."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = ROOT / "include" / "dla.h"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2309_07235_amd import binding
+    return binding
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    text = text.split('extern "C" {', 1)[1]
+    names = re.findall(r"\b([a-z_0-9]+)\s*\([^;{}]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_header_declares_the_boundary():
+    names = _declared_functions()
+    for must in ("lu_factor", "cholesky_factor", "mm3", "mm3_workspace_bytes", "factor_workspace_bytes",
+                 "dla_gemm", "dla_enumerate_tiles", "dla_gemm_params_supported", "dla_default_params",
+                 "dla_strerror"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(B):
+    for name in _declared_functions():
+        assert hasattr(B.lib, name), f"{name} declared in dla.h but not exported"
+
+
+def test_version_and_strerror(B):
+    assert "gfx950" in B.version()
+    assert B.strerror(0) == "success"
+    assert "menu" in B.strerror(B.DLA_ERR_UNSUPPORTED_PARAMS)
+    assert "argument" in B.strerror(-3)
+
+
+def test_tile_menu_queries(B):
+    tiles = B.enumerate_tiles(B.DLA_F64)
+    assert len(tiles) >= 20
+    shapes = {(t.tile_m, t.tile_n) for t in tiles}
+    assert (16, 16) in shapes and (128, 128) in shapes  # the 16x16 tile of the small 3mm config is legal
+    for t in tiles:
+        assert B.gemm_params_supported(B.DLA_F64, t)
+        assert t.tile_m % 16 == 0 and t.tile_n % 16 == 0 and t.tile_k % 4 == 0
+    assert len(B.enumerate_tiles(B.DLA_F32)) >= len(tiles)  # fp32 tiles need less LDS
+    # the paper's own candidates are divisors of the matrix size; most are not MFMA aligned and are refused
+    for bad in ((5, 25), (125, 50), (400, 50), (1, 2000), (48, 48)):
+        assert not B.gemm_params_supported(B.DLA_F64, B.GemmParams(bad[0], bad[1], 0, 0, 0, 0))
+    assert B.gemm_params_supported(B.DLA_F64, B.GemmParams(0, 0, 0, 0, 0, 0))  # all defaults
+    assert not B.gemm_params_supported(B.DLA_F64, B.GemmParams(128, 128, 12, 0, 0, 0))
+    assert not B.gemm_params_supported(B.DLA_F64, B.GemmParams(256, 128, 32, 0, 0, 0))  # exceeds LDS in fp64
+    assert B.gemm_params_supported(B.DLA_F32, B.GemmParams(256, 128, 32, 0, 0, 0))
+    assert not B.gemm_params_supported(7, B.GemmParams(0, 0, 0, 0, 0, 0))
+
+
+def test_block_sizes(B):
+    legal = [nb for nb in range(0, 300) if B.block_size_supported(B.DLA_F64, nb)]
+    assert legal == list(range(16, 129, 16))
+
+
+def test_default_params(B):
+    p = B.default_params(B.DLA_KERNEL_MM3, 2000)
+    assert p.e.as_tuple() == p.f.as_tuple() == p.g.as_tuple()
+    assert B.gemm_params_supported(B.DLA_F64, p.e)
+    for k in (B.DLA_KERNEL_LU, B.DLA_KERNEL_CHOLESKY):
+        f = B.default_params(k, 4000)
+        assert B.block_size_supported(B.DLA_F64, f.nb)
+        assert B.gemm_params_supported(B.DLA_F64, f.update)
+        assert f.lookahead in (0, 1)
+
+
+def test_workspace_queries(B):
+    assert B.mm3_workspace_bytes(1600, 1800, 2200, B.DLA_F64) >= (1600 * 1800 + 1800 * 2200) * 8
+    assert B.mm3_workspace_bytes(1600, 1800, 2200, B.DLA_F32) >= (1600 * 1800 + 1800 * 2200) * 4
+    assert B.mm3_workspace_bytes(-1, 2, 3, B.DLA_F64) == 0
+    assert B.factor_workspace_bytes(4000, B.DLA_F64) > 0
+    assert B.factor_workspace_bytes(-1, B.DLA_F64) == 0
+
+
+def test_argument_errors_are_reported_without_gpu_work(B):
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)  # never dereferenced: every call below fails validation first
+    L = B.lib
+    assert L.lu_factor(None, 8, 8, B.DLA_F64, None, fake, 1 << 20, None, None) == -1
+    assert L.lu_factor(fake, -1, 8, B.DLA_F64, None, fake, 1 << 20, None, None) == -2
+    assert L.lu_factor(fake, 8, 7, B.DLA_F64, None, fake, 1 << 20, None, None) == -3
+    assert L.lu_factor(fake, 8, 8, 5, None, fake, 1 << 20, None, None) == -4
+    assert L.cholesky_factor(fake, 8, 4, B.DLA_F64, None, fake, 1 << 20, None, None) == -3
+    assert L.lu_factor(vp(0x1004), 8, 8, B.DLA_F64, None, fake, 1 << 20, None, None) == -1  # misaligned
+    bad = B.FactorParams(100, 0, B.GemmParams(0, 0, 0, 0, 0, 0))
+    assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    bad = B.FactorParams(64, 0, B.GemmParams(48, 48, 0, 0, 0, 0))
+    assert L.cholesky_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    assert L.lu_factor(fake, 512, 512, B.DLA_F64, None, None, 0, None, None) == B.DLA_ERR_WORKSPACE
+    assert L.lu_factor(fake, 512, 512, B.DLA_F64, None, fake, 16, None, None) == B.DLA_ERR_WORKSPACE
+    # n == 0 is a successful no-op that touches nothing
+    assert L.lu_factor(None, 0, 1, B.DLA_F64, None, None, 0, None, None) == 0
+    assert L.cholesky_factor(None, 0, 1, B.DLA_F64, None, None, 0, None, None) == 0
+
+    def mm3(a=fake, lda=8, b=fake, ldb=8, c=fake, ldc=8, d=fake, ldd=8, g=fake, ldg=8, dims=(8, 8, 8, 8, 8),
+            dt=B.DLA_F64, p=None, ws=fake, wsb=1 << 20):
+        return L.mm3(a, lda, b, ldb, c, ldc, d, ldd, g, ldg, *dims, dt, p, ws, wsb, None)
+
+    assert mm3(a=None) == -1
+    assert mm3(lda=7) == -2
+    assert mm3(b=None) == -3
+    assert mm3(ldb=3) == -4
+    assert mm3(c=None) == -5
+    assert mm3(ldc=3) == -6
+    assert mm3(d=None) == -7
+    assert mm3(ldd=3) == -8
+    assert mm3(g=None) == -9
+    assert mm3(ldg=3) == -10
+    assert mm3(dims=(-1, 8, 8, 8, 8)) == -11
+    assert mm3(dims=(8, 8, 8, 8, -2)) == -15
+    assert mm3(dt=9) == -16
+    assert mm3(ws=None) == B.DLA_ERR_WORKSPACE
+    assert mm3(wsb=64) == B.DLA_ERR_WORKSPACE
+    assert mm3(ws=vp(0x1008)) == B.DLA_ERR_WORKSPACE
+    badp = B.Mm3Params(B.GemmParams(16, 16, 0, 0, 0, 0), B.GemmParams(5, 25, 0, 0, 0, 0), B.GemmParams(0, 0, 0, 0, 0, 0))
+    assert mm3(p=ctypes.byref(badp)) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    assert mm3(dims=(0, 8, 8, 8, 8), a=None, g=None, ws=None, wsb=0) == 0  # empty G: nothing to do
+
+    assert L.dla_gemm(7, fake, 8, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -1
+    assert L.dla_gemm(0, None, 8, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -2
+    assert L.dla_gemm(0, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3
+    assert L.dla_gemm(2, fake, 8, fake, 8, fake, 8, 8, 6, 8, B.DLA_F64, None, None) == -9
+    assert L.dla_gemm(0, fake, 8, fake, 8, fake, 8, 0, 8, 8, B.DLA_F64, None, None) == 0
+    ms = ctypes.c_double()
+    assert L.dla_profile_read(9, ctypes.byref(ms), None, None) == -1
