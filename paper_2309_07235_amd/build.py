@@ -33,9 +33,13 @@ def _tile_menu():
     return [tuple(int(v) for v in m.groups()) for m in re.finditer(r"X\((\d+), (\d+), (\d+), (\d+)\)", body)]
 
 
-def _headers_hash() -> str:
+GEMM_HEADERS = ("dla_common.hpp", "gemm_kernel.hpp", "gemm_dispatch.hpp", "dla_codes.hpp")
+
+
+def _headers_hash(gemm_only: bool = False) -> str:
     h = hashlib.sha256()
-    for p in sorted(list(CSRC.glob("*.hpp")) + [HERE.parent / "include" / "dla.h"]):
+    headers = [CSRC / n for n in GEMM_HEADERS] if gemm_only else sorted(CSRC.glob("*.hpp"))
+    for p in list(headers) + [HERE.parent / "include" / "dla.h"]:
         h.update(p.read_bytes())
     h.update(" ".join(FLAGS).encode())
     return h.hexdigest()
@@ -58,7 +62,7 @@ def _compile(src: Path, obj: Path, stamp: str, verbose: bool) -> str:
 
 def build(verbose: bool = False, jobs: int | None = None) -> Path:
     BUILD.mkdir(exist_ok=True)
-    hh = _headers_hash()
+    hh_all, hh_gemm = _headers_hash(False), _headers_hash(True)
     units = []
     template = (CSRC / "gemm_inst.hip.in").read_text()
     for tname, ctype in (("f64", "double"), ("f32", "float")):
@@ -76,6 +80,7 @@ def build(verbose: bool = False, jobs: int | None = None) -> Path:
         futs = []
         for src in units:
             obj = BUILD / (src.stem + ".o")
+            hh = hh_gemm if src.name.startswith("gemm_") else hh_all
             stamp = hashlib.sha256((hh + src.read_text()).encode()).hexdigest()
             objs.append(obj)
             futs.append(ex.submit(_compile, src, obj, stamp, verbose))

@@ -1,0 +1,310 @@
+"""GPU parity of lu_factor and cholesky_factor against the CPU oracle."""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2309_07235_amd import inputs
+from tests.gpu_util import announce, to_device, to_host
+from tests.metrics import EPS32, EPS64, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL64 = 1e-9   # max relative error, denominator floored at the RMS of the expected factor entries
+TOL32 = 1e-4
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked.json")
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2309_07235_amd import binding
+    return binding
+
+
+def _fparams(B, nb=0, lookahead=-1, tile=None):
+    t = B.GemmParams(*(tile or (0, 0)), *([0] * (6 - len(tile or (0, 0)))))
+    return B.FactorParams(nb, lookahead, t)
+
+
+def _gpu_lu(B, A, params=None, dtype=None, want_info=True):
+    import torch
+    a = to_device(A, dtype)
+    info = torch.full((1,), -99, dtype=torch.int32, device="cuda") if want_info else None
+    B.lu_factor(a, params, info=info)
+    out = to_host(a)
+    return out, (int(info.item()) if want_info else None)
+
+
+def _gpu_chol(B, A, params=None, dtype=None, want_info=True):
+    import torch
+    a = to_device(A, dtype)
+    info = torch.full((1,), -99, dtype=torch.int32, device="cuda") if want_info else None
+    B.cholesky_factor(a, params, info=info)
+    out = to_host(a)
+    return out, (int(info.item()) if want_info else None)
+
+
+def _check_lu(oracle, got, A, n, tol=TOL64, eps=EPS64):
+    want, info = oracle.lu(A)
+    assert info == 0
+    assert max_rel_err(got, want) <= tol
+    assert oracle.lu_residual(A, got) <= 10 * max(n, 1) * eps
+
+
+def _check_chol(oracle, got, A, n, tol=TOL64, eps=EPS64):
+    want, info = oracle.cholesky(A)
+    assert info == 0
+    low = np.tril(np.ones((n, n), dtype=bool))
+    assert max_rel_err(got[low], want[low]) <= tol
+    assert np.all(got[~low] == 0.0), "strict upper triangle must be exactly zero"
+    assert oracle.cholesky_residual(A, got) <= 10 * max(n, 1) * eps
+
+
+# ------------------------------------------------------------------ small and ragged sizes
+@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 31, 100, 128, 129, 200, 333])
+@pytest.mark.parametrize("nb", [16, 48, 128])
+def test_lu_small_sizes(B, oracle, n, nb):
+    announce(f"lu n={n} nb={nb}")
+    A = inputs.general_dominant_matrix(n, 100 + n)
+    got, info = _gpu_lu(B, A, _fparams(B, nb))
+    assert info == 0
+    _check_lu(oracle, got, A, n)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 15, 16, 17, 31, 100, 128, 129, 200, 333])
+@pytest.mark.parametrize("nb", [16, 48, 128])
+def test_cholesky_small_sizes(B, oracle, n, nb):
+    announce(f"cholesky n={n} nb={nb}")
+    A = inputs.spd_matrix(n, 200 + n)
+    got, info = _gpu_chol(B, A, _fparams(B, nb))
+    assert info == 0
+    _check_chol(oracle, got, A, n)
+
+
+def test_hand_worked_fixtures_on_gpu(B):
+    announce("hand-worked fixtures")
+    with open(GOLDEN) as f:
+        g = json.load(f)
+    tofloat = lambda m: np.array([[float(Fraction(v)) for v in r] for r in m])
+    for c in g["lu"]:
+        got, info = _gpu_lu(B, tofloat(c["A"]))
+        assert info == 0
+        np.testing.assert_allclose(got, tofloat(c["LU"]), rtol=8 * EPS64, atol=0, err_msg=c["name"])
+    for c in g["cholesky"]:
+        got, info = _gpu_chol(B, tofloat(c["A"]))
+        assert info == 0
+        np.testing.assert_allclose(got, tofloat(c["L"]), rtol=8 * EPS64, atol=0, err_msg=c["name"])
+
+
+# ------------------------------------------------------------------ exact integer matrices, bit for bit
+@pytest.mark.parametrize("n,nb", [(517, 128), (517, 48), (1000, 64), (2048, 128)])
+def test_min_index_matrix_is_bit_exact(B, oracle, n, nb):
+    """A[i][j] = min(i, j) + 1 has all-ones factors; every intermediate is a small integer."""
+    announce(f"min-index exact n={n} nb={nb}")
+    A = inputs.min_index_matrix(n)
+    got, info = _gpu_lu(B, A, _fparams(B, nb))
+    assert info == 0 and np.array_equal(got, np.ones((n, n)))
+    got, info = _gpu_chol(B, A, _fparams(B, nb))
+    assert info == 0 and np.array_equal(got, np.tril(np.ones((n, n))))
+    if n <= 600:  # and the oracle agrees with the closed form at this size
+        assert np.array_equal(oracle.lu(A)[0], np.ones((n, n)))
+
+
+def test_pascal_matrix_is_bit_exact(B, oracle):
+    announce("pascal 14")
+    n = 14
+    S = np.array([[math.comb(i + j, i) for j in range(n)] for i in range(n)], dtype=np.float64)
+    got, info = _gpu_chol(B, S)
+    want, _ = oracle.cholesky(S)
+    assert info == 0 and np.array_equal(got, want)
+    got, info = _gpu_lu(B, S)
+    want, _ = oracle.lu(S)
+    assert info == 0 and np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ the named configurations
+def test_cholesky_n1024_nb64(B, oracle):
+    announce("cholesky N=1024 nb=64")
+    A = inputs.spd_matrix(1024, 2)
+    got, info = _gpu_chol(B, A, _fparams(B, 64))
+    assert info == 0
+    _check_chol(oracle, got, A, 1024)
+
+
+def test_lu_n2000_nb128(B, oracle):
+    announce("lu N=2000 nb=128 (last block 80)")
+    A = inputs.diag_dominant_matrix(2000, 3)
+    got, info = _gpu_lu(B, A, _fparams(B, 128))
+    assert info == 0
+    _check_lu(oracle, got, A, 2000)
+
+
+@pytest.mark.parametrize("lookahead", [0, 1])
+def test_n4000_both(B, oracle, lookahead):
+    """The size the headline metric is quoted on, in the launch configuration the benchmark uses."""
+    announce(f"lu + cholesky N=4000 lookahead={lookahead}")
+    A = inputs.diag_dominant_matrix(4000, 5)
+    got, info = _gpu_lu(B, A, _fparams(B, 0, lookahead))
+    assert info == 0
+    _check_lu(oracle, got, A, 4000)
+    S = inputs.spd_matrix(4000, 5)
+    got, info = _gpu_chol(B, S, _fparams(B, 0, lookahead))
+    assert info == 0
+    _check_chol(oracle, got, S, 4000)
+
+
+def test_n8192_properties(B, oracle):
+    """N=8192: exact all-ones factors of the min-index matrix, and a randomised O(N^2)
+    reconstruction check of the seeded random inputs with the oracle's matrix-vector routines."""
+    n = 8192
+    announce("N=8192 min-index exact")
+    A = inputs.min_index_matrix(n)
+    got, info = _gpu_lu(B, A)
+    assert info == 0 and np.array_equal(got, np.ones((n, n)))
+    got, info = _gpu_chol(B, A)
+    assert info == 0 and np.array_equal(got, np.tril(np.ones((n, n))))
+    del A, got
+    announce("N=8192 LU reconstruction")
+    A = inputs.diag_dominant_matrix(n, 6)
+    lu, info = _gpu_lu(B, A)
+    assert info == 0
+    for t in range(4):
+        x = inputs.uniform_matrix(6, 50 + t, n, 1).ravel()
+        y0 = oracle.matvec(A, x)
+        y1 = oracle.lu_apply(lu, x)
+        assert np.linalg.norm(y0 - y1) <= 10 * n * EPS64 * np.linalg.norm(y0)
+    announce("N=8192 LU sampled rows against the oracle's full factorisation")
+    want, _ = oracle.lu(A)
+    assert max_rel_err(lu, want) <= TOL64
+    del want, lu
+    announce("N=8192 Cholesky reconstruction")
+    A[np.diag_indices(n)] += 1.0 - float(n)  # same Gram matrix, +I instead of +N*I: the SPD generator
+    L, info = _gpu_chol(B, A)
+    assert info == 0
+    assert np.all(np.triu(L, 1) == 0.0)
+    for t in range(4):
+        x = inputs.uniform_matrix(6, 60 + t, n, 1).ravel()
+        y0 = oracle.symv_lower(A, x)
+        y1 = oracle.cholesky_apply(L, x)
+        assert np.linalg.norm(y0 - y1) <= 10 * n * EPS64 * np.linalg.norm(y0)
+
+
+# ------------------------------------------------------------------ schedules
+@pytest.mark.parametrize("tile", [(16, 16), (64, 64), (128, 128), (128, 64), (256, 128)])
+def test_update_schedules(B, oracle, tile):
+    announce(f"factor update tile {tile}")
+    n = 700
+    A = inputs.general_dominant_matrix(n, 31)
+    got, info = _gpu_lu(B, A, _fparams(B, 64, 0, tile))
+    assert info == 0
+    _check_lu(oracle, got, A, n)
+    if tile[0] == tile[1]:
+        S = inputs.spd_matrix(n, 32)
+        got, info = _gpu_chol(B, S, _fparams(B, 64, 0, tile))
+        assert info == 0
+        _check_chol(oracle, got, S, n)
+
+
+def test_rectangular_tile_is_refused_for_cholesky(B):
+    import torch
+    a = to_device(inputs.spd_matrix(64, 1))
+    with pytest.raises(B.DlaError) as e:
+        B.cholesky_factor(a, _fparams(B, 64, 0, (128, 64)))
+    assert e.value.code == B.DLA_ERR_UNSUPPORTED_PARAMS
+
+
+# ------------------------------------------------------------------ breakdown reporting
+def test_zero_pivot_index_matches_oracle(B, oracle):
+    announce("lu zero pivot")
+    n, k = 300, 201
+    A = inputs.general_dominant_matrix(n, 40)
+    A[k, :] = A[k - 1, :]  # rows k-1 and k equal: pivot k (0-based) becomes exactly zero
+    A[:, k] = A[:, k - 1]
+    A[k, k] = A[k - 1, k - 1]
+    want_info = oracle.lu(A)[1]
+    assert want_info == k + 1
+    _, info = _gpu_lu(B, A, _fparams(B, 64))
+    assert info == want_info
+    _, info = _gpu_lu(B, np.zeros((5, 5)))
+    assert info == 1
+
+
+def test_indefinite_matrix_index_matches_oracle(B, oracle):
+    announce("cholesky non-positive pivot")
+    n, k = 260, 150
+    S = inputs.spd_matrix(n, 41)
+    S[k, k] = -5.0
+    want_info = oracle.cholesky(S)[1]
+    assert want_info == k + 1
+    _, info = _gpu_chol(B, S, _fparams(B, 64))
+    assert info == want_info
+    _, info = _gpu_chol(B, -np.eye(3))
+    assert info == 1
+
+
+def test_info_pointer_is_optional(B, oracle):
+    announce("info=NULL")
+    A = inputs.general_dominant_matrix(90, 42)
+    got, _ = _gpu_lu(B, A, want_info=False)
+    _check_lu(oracle, got, A, 90)
+
+
+# ------------------------------------------------------------------ layout, streams, determinism
+def test_cholesky_ignores_upper_triangle(B, oracle):
+    announce("cholesky upper junk")
+    n = 301
+    S = inputs.spd_matrix(n, 43)
+    junk = np.tril(S) + np.triu(np.full((n, n), np.nan), 1)
+    got, info = _gpu_chol(B, junk, _fparams(B, 64))
+    assert info == 0
+    _check_chol(oracle, got, S, n)
+
+
+def test_leading_dimension_and_stream(B, oracle):
+    import torch
+    announce("lda > n, side stream")
+    n, pad = 273, 11
+    A = inputs.general_dominant_matrix(n, 44)
+    buf = torch.full((n, n + pad), -3.0, dtype=torch.float64, device="cuda")
+    buf[:, :n] = to_device(A)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        B.lu_factor(buf[:, :n], _fparams(B, 64))
+    s.synchronize()
+    out = to_host(buf)
+    _check_lu(oracle, out[:, :n], A, n)
+    assert np.all(out[:, n:] == -3.0)
+
+
+def test_repeated_calls_are_bitwise_identical(B):
+    announce("determinism")
+    A = inputs.diag_dominant_matrix(1500, 45)
+    a, _ = _gpu_lu(B, A)
+    b, _ = _gpu_lu(B, A)
+    assert np.array_equal(a, b)
+    S = inputs.spd_matrix(1500, 45)
+    a, _ = _gpu_chol(B, S)
+    b, _ = _gpu_chol(B, S)
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ fp32 variant
+@pytest.mark.parametrize("n,nb", [(500, 128), (1000, 64)])
+def test_fp32_factorisations(B, oracle, n, nb):
+    """fp32 kernels against the fp64 oracle applied to the fp32-rounded input."""
+    import torch
+    announce(f"fp32 n={n} nb={nb}")
+    A32 = inputs.diag_dominant_matrix(n, 46).astype(np.float32)
+    got, info = _gpu_lu(B, A32, _fparams(B, nb), dtype=torch.float32)
+    assert info == 0 and got.dtype == np.float32
+    _check_lu(oracle, got.astype(np.float64), A32.astype(np.float64), n, TOL32, EPS32)
+    S32 = inputs.spd_matrix(n, 47).astype(np.float32)
+    got, info = _gpu_chol(B, S32, _fparams(B, nb), dtype=torch.float32)
+    assert info == 0
+    _check_chol(oracle, got.astype(np.float64), S32.astype(np.float64), n, TOL32, EPS32)
