@@ -137,6 +137,7 @@ size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt);
  *   op 2:  lower(C) -= A*B^T   A m x k, B n x k, m == n; tiles that lie strictly
  *          above the diagonal are skipped, the upper part of diagonal tiles
  *          is computed too (the Cholesky trailing update)
+ *   op 3:  C -= A*B^T          A m x k, B n x k, every tile (the Cholesky look-ahead panel update)
  * C must not overlap A or B.
  */
 int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c,

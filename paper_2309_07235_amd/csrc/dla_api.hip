@@ -59,7 +59,8 @@ int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedu
   for (int i = 0; i < kNumKu; ++i) ku_ok |= (kKu[i].tk == s.tk && kKu[i].uk == s.uk);
   if (!tile_ok || !ku_ok) return DLA_ERR_UNSUPPORTED_PARAMS;
   if (op == OP_SUB_NT_LOWER && s.tm != s.tn) return DLA_ERR_UNSUPPORTED_PARAMS;
-  if (gemm_lds_bytes(s, op == OP_SUB_NT_LOWER, esize(dt)) > kMaxLdsBytes) return DLA_ERR_UNSUPPORTED_PARAMS;
+  if (gemm_lds_bytes(s, op == OP_SUB_NT_LOWER || op == OP_SUB_NT, esize(dt)) > kMaxLdsBytes)
+    return DLA_ERR_UNSUPPORTED_PARAMS;
   *out = s;
   return DLA_SUCCESS;
 }
@@ -260,7 +261,7 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
 
 int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c, int64_t ldc, int64_t m,
              int64_t n, int64_t k, dla_dtype dt, const dla_gemm_params* p, void* hip_stream) {
-  if (op < OP_ASSIGN || op > OP_SUB_NT_LOWER) return -1;
+  if (op < OP_ASSIGN || op > OP_SUB_NT) return -1;
   if (m < 0) return -8;
   if (n < 0) return -9;
   if (k < 0) return -10;
@@ -272,7 +273,7 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   if (!empty && k > 0 && !d_b) return -4;
   if (!empty && !d_c) return -6;
   if (lda < (k > 0 ? k : 1)) return -3;
-  if (ldb < (op == OP_SUB_NT_LOWER ? (k > 0 ? k : 1) : (n > 0 ? n : 1))) return -5;
+  if (ldb < ((op == OP_SUB_NT_LOWER || op == OP_SUB_NT) ? (k > 0 ? k : 1) : (n > 0 ? n : 1))) return -5;
   if (ldc < (n > 0 ? n : 1)) return -7;
   const size_t es = (size_t)esize(dt);
   if (((uintptr_t)d_a % es) || ((uintptr_t)d_b % es)) return -2;

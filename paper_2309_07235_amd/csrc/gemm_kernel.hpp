@@ -12,13 +12,13 @@
 // LDS layouts.  A rows keep k contiguous with an odd row stride (TK+1): the
 // 16 lanes that read one fragment column then hit 16 distinct bank pairs.
 // B (k x n) keeps n contiguous: a fragment row is one contiguous 128-byte run.
-// For OP_SUB_NT the right operand is stored like A.
+// For the A*B^T forms the right operand is stored like A.
 #pragma once
 #include "dla_common.hpp"
 
 namespace dla {
 
-enum GemmOp { OP_ASSIGN = 0, OP_SUB = 1, OP_SUB_NT_LOWER = 2 };
+enum GemmOp { OP_ASSIGN = 0, OP_SUB = 1, OP_SUB_NT_LOWER = 2, OP_SUB_NT = 3 };
 
 template <typename T>
 struct GemmProblem {
@@ -74,19 +74,18 @@ struct RowTileLoader {
       }
     }
   }
+  // Edge tiles: every load is issued unconditionally from an address clamped into the valid
+  // part (rows_valid, k_valid >= 1) and zeroed afterwards, so no load waits behind a branch.
   __device__ inline void load_edge(const T* __restrict__ base, int64_t ld, int tid, int rows_valid, int k_valid) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
-      r[it][0] = T(0);
-      r[it][1] = T(0);
       if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int row = idx / VPR, c2 = idx % VPR;
-        if (row < rows_valid) {
-          const T* p = base + (int64_t)row * ld + 2 * c2;
-          if (2 * c2 < k_valid) r[it][0] = p[0];
-          if (2 * c2 + 1 < k_valid) r[it][1] = p[1];
-        }
+        const int row = idx / VPR, c0 = 2 * (idx % VPR), c1 = c0 + 1;
+        const T* p = base + (int64_t)(row < rows_valid ? row : rows_valid - 1) * ld;
+        const T x0 = p[c0 < k_valid ? c0 : k_valid - 1], x1 = p[c1 < k_valid ? c1 : k_valid - 1];
+        r[it][0] = (row < rows_valid && c0 < k_valid) ? x0 : T(0);
+        r[it][1] = (row < rows_valid && c1 < k_valid) ? x1 : T(0);
       }
     }
   }
@@ -130,15 +129,12 @@ struct ColTileLoader {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
-      r[it][0] = T(0);
-      r[it][1] = T(0);
       if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int kr = idx / VPR, c2 = idx % VPR;
-        if (kr < k_valid) {
-          const T* p = base + (int64_t)kr * ld + 2 * c2;
-          if (2 * c2 < cols_valid) r[it][0] = p[0];
-          if (2 * c2 + 1 < cols_valid) r[it][1] = p[1];
-        }
+        const int kr = idx / VPR, c0 = 2 * (idx % VPR), c1 = c0 + 1;
+        const T* p = base + (int64_t)(kr < k_valid ? kr : k_valid - 1) * ld;
+        const T x0 = p[c0 < cols_valid ? c0 : cols_valid - 1], x1 = p[c1 < cols_valid ? c1 : cols_valid - 1];
+        r[it][0] = (kr < k_valid && c0 < cols_valid) ? x0 : T(0);
+        r[it][1] = (kr < k_valid && c1 < cols_valid) ? x1 : T(0);
       }
     }
   }
@@ -165,7 +161,8 @@ gemm_kernel(const GemmGroup<T> g) {
   constexpr int NW = (TM / WM) * WAVES_N;
   constexpr int NT = NW * 64;
   constexpr int FM = WM / 16, FN = WN / 16, KSTEPS = TK / 4;
-  constexpr bool BT = (OP == OP_SUB_NT_LOWER);
+  constexpr bool BT = (OP == OP_SUB_NT_LOWER || OP == OP_SUB_NT);
+  constexpr bool LOWER = (OP == OP_SUB_NT_LOWER);
   constexpr bool SUB = (OP != OP_ASSIGN);
   using L = GemmLds<TM, TN, TK, WM, WN, BT, (int)sizeof(T)>;
   using acc_t = typename Mfma<T>::acc_t;
@@ -179,7 +176,7 @@ gemm_kernel(const GemmGroup<T> g) {
   const GemmProblem<T>& P = g.prob[pi];
   const int local = logical - P.tile_begin;
   int ti, tj;
-  if (BT && TM == TN) {  // lower-triangular tile set, row by row
+  if (LOWER && TM == TN) {  // lower-triangular tile set, row by row
     int i = (int)((sqrtf(8.0f * (float)local + 1.0f) - 1.0f) * 0.5f);
     while ((int64_t)i * (i + 1) / 2 > local) --i;
     while ((int64_t)(i + 1) * (i + 2) / 2 <= local) ++i;
@@ -190,7 +187,7 @@ gemm_kernel(const GemmGroup<T> g) {
     tj = local % P.tiles_n;
   }
   const int m0 = ti * TM, n0 = tj * TN;
-  if (BT && n0 >= m0 + TM) return;  // tile strictly above the diagonal (only when TM != TN)
+  if (LOWER && n0 >= m0 + TM) return;  // tile strictly above the diagonal (only when TM != TN)
 
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
@@ -203,17 +200,29 @@ gemm_kernel(const GemmGroup<T> g) {
   acc_t acc[FM][FN];
   T* const Cw = P.C + (int64_t)(m0 + wm0) * ldc + (n0 + wn0);
   if (SUB) {
+    if (full_mn) {  // interior tile: constant offsets from one base pointer
 #pragma unroll
-    for (int a = 0; a < FM; ++a)
+      for (int a = 0; a < FM; ++a)
 #pragma unroll
-      for (int b = 0; b < FN; ++b)
+        for (int b = 0; b < FN; ++b)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int r = a * 16 + Mfma<T>::row_of(v, lane), c = b * 16 + l15;
-          T x = T(0);
-          if (full_mn || (m0 + wm0 + r < M && n0 + wn0 + c < N)) x = Cw[(int64_t)r * ldc + c];
-          acc[a][b][v] = x;
-        }
+          for (int v = 0; v < 4; ++v)
+            acc[a][b][v] = Cw[(int64_t)(a * 16 + Mfma<T>::row_of(v, lane)) * ldc + b * 16 + l15];
+    } else {  // edge tile: clamped address, masked value, so the preload never branches per element
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int r = a * 16 + Mfma<T>::row_of(v, lane), c = b * 16 + l15;
+            const bool in = (m0 + wm0 + r < M) && (n0 + wn0 + c < N);
+            const int rc = (m0 + wm0 + r < M) ? r : M - 1 - m0 - wm0;
+            const int cc = (n0 + wn0 + c < N) ? c : N - 1 - n0 - wn0;
+            const T x = Cw[(int64_t)rc * ldc + cc];
+            acc[a][b][v] = in ? x : T(0);
+          }
+    }
   } else {
 #pragma unroll
     for (int a = 0; a < FM; ++a)

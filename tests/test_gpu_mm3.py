@@ -161,14 +161,14 @@ def test_strided_operands_and_stream(B, oracle):
     assert np.all(got[:, dims[4]:] == -7.0)  # nothing written outside G
 
 
-@pytest.mark.parametrize("op", [0, 1, 2])
+@pytest.mark.parametrize("op", [0, 1, 2, 3])
 def test_gemm_building_block(B, op):
     """dla_gemm: assign, subtract, and the lower-triangular A*B^T update, against numpy."""
     import torch
     announce(f"dla_gemm op={op}")
     m, n, k = (203, 203, 77) if op == 2 else (203, 157, 77)
     a = inputs.uniform_matrix(20, 0, m, k)
-    b = inputs.uniform_matrix(20, 1, n, k) if op == 2 else inputs.uniform_matrix(20, 1, k, n)
+    b = inputs.uniform_matrix(20, 1, n, k) if op >= 2 else inputs.uniform_matrix(20, 1, k, n)
     c0 = inputs.uniform_matrix(20, 2, m, n)
     for tile in ((128, 128), (64, 64), (16, 16)):
         c = to_device(c0)
@@ -179,7 +179,7 @@ def test_gemm_building_block(B, op):
         elif op == 1:
             want = c0 - a @ b
         else:
-            want = c0 - a @ b.T
+            want = c0 - a @ b.T  # op 2: lower tiles only, op 3: everywhere
         if op == 2:
             low = np.tril(np.ones((m, n), dtype=bool))
             assert max_rel_err(got[low], want[low]) <= TOL64
