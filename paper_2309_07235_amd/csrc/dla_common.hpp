@@ -41,6 +41,15 @@ struct Mfma<float> {
   __device__ static inline int row_of(int v, int lane) { return 4 * (lane >> 4) + v; }
 };
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load
+// and store in flight (its fence covers all address spaces), which would serialise the prefetches
+// these kernels keep running across barriers.
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator complex dies, workgroups are dealt round-robin
 
 // Workgroup id -> logical work item so that each XCD (and its private L2)

@@ -2,6 +2,7 @@
 // column  (1) factor the diagonal block, (2) solve the panels, (3) update the
 // trailing matrix with the MFMA GEMM (the step that dominates the run time).
 #include "factor_kernels.hpp"
+#include "update_kernel.hpp"
 #include "host_common.hpp"
 
 namespace dla {
@@ -45,6 +46,48 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st) {
   }
   ProfileScope scope(PHASE_DIAG, 0.0, st);
   hipLaunchKernelGGL(kern, dim3(1), dim3(kDiagThreads), diag_lds_bytes<T>(), st, a);
+  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+}
+
+// Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp).
+template <typename T, int KIND>
+static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, hipStream_t st) {
+  if (m <= 0) return DLA_SUCCESS;
+  constexpr bool LOWER = (KIND == KIND_CHOL);
+  auto kern = update_kernel<T, LOWER>;
+  using LD = UpdateLds<T, LOWER>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            LD::BYTES) != hipSuccess)
+      return DLA_ERR_HIP;
+    attr_done = true;
+  }
+  UpdateArgs<T> a;
+  a.L = L;
+  a.R = R;
+  a.C = C;
+  a.ld = ld;
+  a.m = (int)m;
+  a.b = b;
+  const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
+  int64_t total_blocks = 0;
+  for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)m, LOWER);
+  // one 8-wave workgroup per compute unit: aim at one full round of at most 256 items
+  const int slots = 256;
+  a.bpi = (int)((total_blocks + slots - 1) / slots);
+  if (a.bpi < 1) a.bpi = 1;
+  int items = 0;
+  for (;;) {
+    items = 0;
+    for (int p = 0; p < npanels; ++p) items += update_items_of_panel(p, (int)m, a.bpi, LOWER);
+    if (items <= slots || a.bpi >= (1 << 20)) break;
+    ++a.bpi;  // rounding up per panel overshot the slot count
+  }
+  a.items = items;
+  const double flops = (LOWER ? 1.0 : 2.0) * (double)m * (double)m * (double)b;
+  ProfileScope scope(PHASE_GEMM, flops, st);
+  hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
@@ -151,6 +194,14 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     return s;
   };
 
+  // m x m trailing update behind the panel whose L21 / U12 are given
+  auto trailing = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, hipStream_t s) -> int {
+    if (auto_tile) return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, s);
+    const GemmSchedule us = update_schedule(mm);
+    if (KIND == KIND_LU) return run_gemm<T>(us, OP_SUB, Lp, lda, Up, lda, Cp, lda, mm, mm, bb, s);
+    return run_gemm<T>(us, OP_SUB_NT_LOWER, Lp, lda, Lp, lda, Cp, lda, mm, mm, bb, s);
+  };
+
   LookaheadCtx* ctx = nullptr;
   if (lookahead && n > 2 * (int64_t)nb) {
     ctx = &lookahead_ctx();
@@ -198,13 +249,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         if ((rc = run_gemm<T>(ps, OP_SUB_NT, L21, lda, L21, lda, A22, lda, m, bn, b, st)) != DLA_SUCCESS) return rc;
       }
       T* const C = A22 + bn * lda + bn;
-      const GemmSchedule us = update_schedule(mr);
-      if (KIND == KIND_LU)
-        rc = run_gemm<T>(us, OP_SUB, L21 + bn * lda, lda, U12 + bn, lda, C, lda, mr, mr, b, ctx->helper);
-      else
-        rc = run_gemm<T>(us, OP_SUB_NT_LOWER, L21 + bn * lda, lda, L21 + bn * lda, lda, C, lda, mr, mr, b,
-                         ctx->helper);
-      if (rc != DLA_SUCCESS) return rc;
+      if ((rc = trailing(L21 + bn * lda, U12 + bn, C, mr, b, ctx->helper)) != DLA_SUCCESS) return rc;
       if (hipEventRecord(e_bulk, ctx->helper) != hipSuccess) return DLA_ERR_HIP;
       bulk_pending = true;
       // next panel right behind the strip update, on the caller's stream
@@ -214,12 +259,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         if (hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
         bulk_pending = false;
       }
-      const GemmSchedule us = update_schedule(m);
-      if (KIND == KIND_LU)
-        rc = run_gemm<T>(us, OP_SUB, L21, lda, U12, lda, A22, lda, m, m, b, st);
-      else
-        rc = run_gemm<T>(us, OP_SUB_NT_LOWER, L21, lda, L21, lda, A22, lda, m, m, b, st);
-      if (rc != DLA_SUCCESS) return rc;
+      if ((rc = trailing(L21, U12, A22, m, b, st)) != DLA_SUCCESS) return rc;
       if ((rc = panel(k0 + b, step + 1, st)) != DLA_SUCCESS) return rc;
     }
   }

@@ -263,7 +263,7 @@ gemm_kernel(const GemmGroup<T> g) {
     fetch(0);
     stash(0);
   }
-  __syncthreads();
+  lds_barrier();
 
   for (int s = 0; s < nslab; ++s) {
     const bool more = (s + 1 < nslab);
@@ -285,7 +285,7 @@ gemm_kernel(const GemmGroup<T> g) {
         for (int b = 0; b < FN; ++b) acc[a][b] = Mfma<T>::mma(fa[a], fb[b], acc[a][b]);
     }
     if (more) stash((s + 1) & 1);
-    __syncthreads();
+    lds_barrier();
   }
 
   // ---- store ---------------------------------------------------------------------

@@ -1,0 +1,333 @@
+// Trailing-matrix update of the blocked factorisations, specialised for its shape:
+//   LU:        A22 (m x m)       -= L21 (m x b) * U12 (b x m)
+//   Cholesky:  lower(A22)        -= L21 * L21^T
+// with b = block size <= 128, so the product is a rank-b update that streams the trailing matrix
+// once (read + write) for 2*b flops per element: 16 flop/byte at b = 128 in fp64, just above the
+// MFMA/HBM ridge.  The generic LDS-tiled GEMM re-stages both operands for every output tile and
+// loads its C tile up front; here the left panel never moves:
+//
+//   - a workgroup (8 waves) owns 128 rows of L21; every wave keeps its 16 x b slice as MFMA
+//     left-operand fragments IN REGISTERS (negated, so the accumulators can start from C);
+//   - the workgroup then walks a range of 32-column blocks of the trailing matrix: the b x 32
+//     block of the right operand is staged through double-buffered LDS, the 16 x 32 block of C per
+//     wave is prefetched into registers one iteration ahead, 64 MFMAs per wave and iteration
+//     run from registers + LDS, and the finished block is stored while the next one computes.
+//   - the eight waves form two groups of four (one wave of each group per SIMD) that take turns
+//     on the MFMA pipes: while one group multiplies a column block, the other stores its previous
+//     result, fetches its share of the next right-operand block and its next C block, and writes
+//     the share to LDS; two barriers per block keep the groups in anti-phase.
+//
+// Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone.
+#pragma once
+#include <type_traits>
+#include "dla_common.hpp"
+
+// Optional phase tracing for development harnesses; expands to nothing in the library build.
+#ifndef DLA_TRACE
+#define DLA_TRACE(i)
+#endif
+
+namespace dla {
+
+constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
+constexpr int kUpdCols = 32;    // columns per iteration
+constexpr int kUpdThreads = 512;
+constexpr int kUpdKMax = 128;   // largest block size b
+
+template <typename T>
+struct UpdateArgs {
+  const T* L;   // m x b left panel (L21)
+  const T* R;   // LU: b x m right panel (U12);  Cholesky: the same m x b panel as L
+  T* C;         // m x m trailing matrix
+  int64_t ld;   // common leading dimension (all three live in the same matrix)
+  int m, b;
+  int bpi;      // target number of 32-column blocks per work item
+  int items;    // number of work items = grid size
+};
+
+template <typename T, bool LOWER>
+struct UpdateLds {
+  // The b x 32 right-operand block is stored in MFMA fragment order: element (k, col) sits at
+  // ((k/4)*2 + col/16)*64 + (k%4)*16 + col%16, i.e. the 64 values one wave reads for k-step k/4 and
+  // column block col/16 are contiguous in lane order, so fragment reads are conflict free.
+  static constexpr int B_ELEMS = kUpdKMax * kUpdCols;
+  static constexpr int B_PAD = B_ELEMS;
+  // the left panel is staged through the same memory, 64 k-columns at a time: [rows][65]
+  static constexpr int A_HALF = kUpdRows * 65;
+  static constexpr int ELEMS = (2 * B_PAD > A_HALF) ? 2 * B_PAD : A_HALF;
+  static constexpr int BYTES = ELEMS * (int)sizeof(T);
+};
+
+// 32-column blocks row panel p (0-based) has to update, and the number of work items it is cut into
+__host__ __device__ inline int update_blocks_of_panel(int p, int m, bool lower) {
+  const int width = lower ? ((p + 1) * kUpdRows < m ? (p + 1) * kUpdRows : m) : m;
+  return (width + kUpdCols - 1) / kUpdCols;
+}
+__host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool lower) {
+  return (update_blocks_of_panel(p, m, lower) + bpi - 1) / bpi;
+}
+
+template <typename T, bool LOWER>
+__global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
+  using acc_t = typename Mfma<T>::acc_t;
+  using LD = UpdateLds<T, LOWER>;
+  constexpr int KSTEPS = kUpdKMax / 4;  // 32
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  T* const smem = reinterpret_cast<T*>(smem_raw);
+
+  const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l15 = lane & 15, l4 = lane >> 4;
+  const int m = g.m, b = g.b;
+  const int64_t ld = g.ld;
+
+  // ---- which work item: (row panel, first column, one-past-last column) ----------------------
+  const int npanels = (m + kUpdRows - 1) / kUpdRows;
+  int item = xcd_contiguous_id((int)blockIdx.x, g.items);
+  int panel = 0, cnt = 0;
+  for (;;) {
+    cnt = update_items_of_panel(panel, m, g.bpi, LOWER);
+    if (item < cnt || panel + 1 >= npanels) break;
+    item -= cnt;
+    ++panel;
+  }
+  const int row0 = panel * kUpdRows;
+  // The panel's column blocks are dealt round-robin to its items: item q takes blocks q, q + cnt,
+  // q + 2*cnt, ...  Items run side by side, so at any moment the items of one panel touch a run of
+  // adjacent 256-byte pieces of the same matrix rows (DRAM page locality), and every panel is at
+  // about the same right-operand block (L2 reuse).
+  const int nblocks = update_blocks_of_panel(panel, m, LOWER);
+  const int width = LOWER ? ((panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m) : m;
+  const int col_begin = item * kUpdCols;         // first block of this item
+  const int col_step = cnt * kUpdCols;           // distance between its blocks
+  const int col_end = width;                     // a block is valid while its first column is < width
+  (void)nblocks;
+  if (col_begin >= col_end) return;  // uniform
+
+  DLA_TRACE(0);
+  // ---- left panel -> registers (through LDS for coalesced global reads) -----------------------
+  T afrag[KSTEPS];
+  const int wrow0 = row0 + wave * 16;  // first row of this wave
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    {  // rows x 64 k-columns: thread -> (row, 2 adjacent columns); the threads cover RPP rows per pass
+      constexpr int RPP = kUpdThreads / 32, PASSES = kUpdRows / RPP;
+      static_assert(PASSES == 8, "staging registers");
+      const int cp = (tid & 31) * 2, r0 = tid >> 5;
+      T v0[8], v1[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int r = r0 + it * RPP;
+        const int gr = (row0 + r < m) ? row0 + r : m - 1;
+        const int k0 = half * 64 + cp, k1 = k0 + 1;
+        const T* p = g.L + (int64_t)gr * ld;
+        v0[it] = p[k0 < b ? k0 : b - 1];
+        v1[it] = p[k1 < b ? k1 : b - 1];
+        if (!(row0 + r < m && k0 < b)) v0[it] = T(0);
+        if (!(row0 + r < m && k1 < b)) v1[it] = T(0);
+      }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int r = r0 + it * RPP;
+        smem[r * 65 + cp] = -v0[it];
+        smem[r * 65 + cp + 1] = -v1[it];
+      }
+    }
+    lds_barrier();
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS / 2; ++kk)
+      afrag[half * (KSTEPS / 2) + kk] = smem[(wave * 16 + l15) * 65 + kk * 4 + l4];
+    lds_barrier();
+  }
+
+  // ---- right-operand block loader: b x 32 block starting at column j0 -> registers -> LDS ------
+  // LU:       rows k of U12, 32 contiguous columns: thread -> (k = tid / 4, 8 columns)
+  // Cholesky: rows j0..j0+31 of L21, b contiguous k: thread -> (row = tid % 32, 8 k-values at (tid / 32) * 8)
+  constexpr int BPT = kUpdKMax * kUpdCols / kUpdThreads;  // 8 elements per thread
+  T bst[BPT];
+  auto fetch_b = [&](int j0) {
+    if (!LOWER) {
+      const int k = tid >> 2, c0 = (tid & 3) * BPT;
+      const T* p = g.R + (int64_t)(k < b ? k : b - 1) * ld;
+      const bool full = (j0 + kUpdCols <= m) && (k < b);
+      if (full) {
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) bst[i] = p[j0 + c0 + i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+          const int c = j0 + c0 + i;
+          const T x = p[c < m ? c : m - 1];
+          bst[i] = (k < b && c < m) ? x : T(0);
+        }
+      }
+    } else {
+      const int r = tid & 31, k0 = (tid >> 5) * BPT;
+      const int gr = (j0 + r < m) ? j0 + r : m - 1;
+      const T* p = g.R + (int64_t)gr * ld;
+      const bool full = (j0 + r < m) && (k0 + BPT <= b);
+      if (full) {
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) bst[i] = p[k0 + i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+          const int k = k0 + i;
+          const T x = p[k < b ? k : b - 1];
+          bst[i] = (j0 + r < m && k < b) ? x : T(0);
+        }
+      }
+    }
+  };
+  auto stash_b = [&](int buf) {
+    T* sb = smem + buf * LD::B_PAD;
+    if (!LOWER) {
+      const int k = tid >> 2, c0 = (tid & 3) * BPT;  // 8 consecutive columns inside one 16-column block
+      T* d = sb + ((k >> 2) * 2 + (c0 >> 4)) * 64 + (k & 3) * 16 + (c0 & 15);
+#pragma unroll
+      for (int i = 0; i < BPT; ++i) d[i] = bst[i];
+    } else {
+      const int col = tid & 31, k0 = (tid >> 5) * BPT;  // 8 consecutive k of one column
+#pragma unroll
+      for (int i = 0; i < BPT; ++i) {
+        const int k = k0 + i;
+        sb[((k >> 2) * 2 + (col >> 4)) * 64 + (k & 3) * 16 + (col & 15)] = bst[i];
+      }
+    }
+  };
+  // ---- C block of this wave: 16 rows x 32 columns = 2 MFMA blocks ---------------------------------
+  T* const Cw = g.C + (int64_t)wrow0 * ld;
+  auto fetch_c = [&](acc_t (&c)[2], int j0) {
+#ifdef DLA_UPD_NO_CLOAD  // development switch: measure the kernel without its C reads
+    c[0] = acc_t{0, 0, 0, 0};
+    c[1] = acc_t{0, 0, 0, 0};
+    return;
+#endif
+    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
+    if (full) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) c[q][v] = Cw[(int64_t)Mfma<T>::row_of(v, lane) * ld + j0 + q * 16 + l15];
+    } else {
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
+          const int rc = (wrow0 + r < m) ? r : m - 1 - wrow0;  // row index stays inside the matrix
+          const T x = Cw[(int64_t)rc * ld + (cc < m ? cc : m - 1)];
+          c[q][v] = (wrow0 + r < m && cc < m) ? x : T(0);
+        }
+    }
+  };
+  auto store_c = [&](const acc_t (&c)[2], int j0) {
+#ifdef DLA_UPD_NO_STORE  // development switch: keep one store per wave so the work is not optimised away
+    if (j0 != col_begin) return;
+#endif
+    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
+        if (full || (wrow0 + r < m && cc < m)) Cw[(int64_t)r * ld + cc] = c[q][v];
+      }
+  };
+  auto multiply = [&](acc_t (&c)[2], int buf) {
+    const T* sb = smem + buf * LD::B_PAD + lane;
+    T f0 = sb[0], f1 = sb[64];
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      T n0 = T(0), n1 = T(0);
+      if (kk + 1 < KSTEPS) {  // fragments of the next k-step are requested before this step's MFMAs issue
+        n0 = sb[(kk + 1) * 128];
+        n1 = sb[(kk + 1) * 128 + 64];
+      }
+      c[0] = Mfma<T>::mma(afrag[kk], f0, c[0]);
+      c[1] = Mfma<T>::mma(afrag[kk], f1, c[1]);
+      f0 = n0;
+      f1 = n1;
+    }
+  };
+  // ---- pipeline over the column blocks, the two wave groups in anti-phase -------------------------
+  //   barrier X_j : block j of the right operand is complete in LDS buffer buf, buffer buf^1 is free
+  //   slot 1      : group 0 multiplies block j | group 1 stores its block j-1, fetches for j+1, fills its share of buf^1
+  //   barrier Y_j
+  //   slot 2      : group 1 multiplies block j | group 0 stores its block j,   fetches for j+1, fills its share of buf^1
+  const int grp = wave >> 2;
+  // the part of a block step that does not need the MFMA pipe
+  // Prefetch distances: the right-operand share in bst is fetched one whole block step before it is
+  // written to LDS, and a C block is fetched two steps before it is multiplied (three accumulator
+  // sets rotate), so neither the LDS write nor the first MFMA of a step waits on a fresh load.
+  auto side_work = [&](acc_t (&done)[2], int jdone, bool have_done, acc_t (&tgt)[2], int jc, int buf) {
+    const int jn = jc + col_step, jnn = jc + 2 * col_step;
+    if (jn < col_end) stash_b(buf ^ 1);  // block jn, fetched during the previous step
+    if (jnn < col_end) fetch_b(jnn);     // block after that
+    if (have_done) store_c(done, jdone);
+    if (jnn < col_end) fetch_c(tgt, jnn);
+  };
+  DLA_TRACE(1);
+  acc_t c0[2], c1[2], c2[2];
+  fetch_b(col_begin);
+  fetch_c(c0, col_begin);
+  stash_b(0);
+  if (col_begin + col_step < col_end) {
+    fetch_b(col_begin + col_step);
+    fetch_c(c1, col_begin + col_step);
+  }
+  lds_barrier();
+  DLA_TRACE(2);
+  int buf = 0;
+  // One block step.  cur holds this block's C; tgt is the set that becomes free in this step and
+  // receives the C block two steps ahead.  Group 0 frees cur's predecessor itself (it stores right
+  // after multiplying); for group 1 the previous block's result still sits in tgt when the step begins.
+  auto block_step = [&](acc_t (&cur)[2], acc_t (&tgt)[2], int jp, int jc, bool first, int b_) {
+    if (grp == 0) {
+      DLA_TRACE(8);
+      multiply(cur, b_);
+      DLA_TRACE(9);
+      lds_barrier();  // Y
+      DLA_TRACE(10);
+      side_work(cur, jc, true, tgt, jc, b_);
+      DLA_TRACE(11);
+      lds_barrier();  // X
+      DLA_TRACE(12);
+    } else {
+      side_work(tgt, jp, !first, tgt, jc, b_);
+      lds_barrier();  // Y
+      multiply(cur, b_);
+      lds_barrier();  // X
+    }
+  };
+  int jp = col_begin, jc = col_begin;
+  bool first = true;
+  for (;;) {
+    block_step(c0, c2, jp, jc, first, buf);
+    buf ^= 1;
+    first = false;
+    jp = jc;
+    jc += col_step;
+    if (jc >= col_end) {
+      if (grp == 1) store_c(c0, jp);
+      break;
+    }
+    block_step(c1, c0, jp, jc, false, buf);
+    buf ^= 1;
+    jp = jc;
+    jc += col_step;
+    if (jc >= col_end) {
+      if (grp == 1) store_c(c1, jp);
+      break;
+    }
+    block_step(c2, c1, jp, jc, false, buf);
+    buf ^= 1;
+    jp = jc;
+    jc += col_step;
+    if (jc >= col_end) {
+      if (grp == 1) store_c(c2, jp);
+      break;
+    }
+  }
+}
+
+}  // namespace dla
