@@ -29,11 +29,20 @@ static const int kNumKu = (int)(sizeof(kKu) / sizeof(kKu[0]));
 
 static int esize(dla_dtype dt) { return dt == DLA_F64 ? 8 : 4; }
 
-int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out) {
+int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out, int64_t m, int64_t n) {
   GemmSchedule s = {0, 0, 0, 0, 0, 0};
   if (in) s = GemmSchedule{in->tile_m, in->tile_n, in->tile_k, in->unroll_k, in->wave_m, in->wave_n};
   if (s.tm < 0 || s.tn < 0 || s.tk < 0 || s.uk < 0 || s.wm < 0 || s.wn < 0) return DLA_ERR_UNSUPPORTED_PARAMS;
-  if (s.tm == 0 && s.tn == 0) s.tm = s.tn = 128;
+  if (s.tm == 0 && s.tn == 0) {
+    // A 128x128 macro-tile needs about four tiles per compute unit to balance the 256 of them;
+    // outputs smaller than that (the 3mm products of the paper's datasets) take 64x64 tiles.
+    const bool small = m > 0 && n > 0 && ((m + 127) / 128) * ((n + 127) / 128) < 4 * 256;
+    s.tm = s.tn = small ? 64 : 128;
+    if (small && s.tk == 0 && s.uk == 0) {
+      s.tk = 16;
+      s.uk = 2;
+    }
+  }
   if (s.tm == 0) s.tm = s.tn;
   if (s.tn == 0) s.tn = s.tm;
   if (s.wm == 0 || s.wn == 0) {  // default wave split: first menu row with this macro-tile
@@ -242,7 +251,7 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
   if (kernel == DLA_KERNEL_MM3) {
     dla_mm3_params* p = static_cast<dla_mm3_params*>(out);
     GemmSchedule s;
-    resolve_schedule(dt, nullptr, OP_ASSIGN, &s);
+    resolve_schedule(dt, nullptr, OP_ASSIGN, &s, n, n);
     const dla_gemm_params gp = {s.tm, s.tn, s.tk, s.uk, s.wm, s.wn};
     p->e = p->f = p->g = gp;
     return DLA_SUCCESS;
@@ -279,7 +288,7 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   if (((uintptr_t)d_a % es) || ((uintptr_t)d_b % es)) return -2;
   if ((uintptr_t)d_c % es) return -6;
   GemmSchedule s;
-  int rc = resolve_schedule(dt, p, op, &s);
+  int rc = resolve_schedule(dt, p, op, &s, m, n);
   if (rc != DLA_SUCCESS) return rc;
   if (empty) return DLA_SUCCESS;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -322,9 +331,9 @@ int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* 
   if (ldg < (nl > 0 ? nl : 1)) return -10;
   GemmSchedule se, sf, sg;
   int rc;
-  if ((rc = resolve_schedule(dt, p ? &p->e : nullptr, OP_ASSIGN, &se)) != DLA_SUCCESS) return rc;
-  if ((rc = resolve_schedule(dt, p ? &p->f : nullptr, OP_ASSIGN, &sf)) != DLA_SUCCESS) return rc;
-  if ((rc = resolve_schedule(dt, p ? &p->g : nullptr, OP_ASSIGN, &sg)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->e : nullptr, OP_ASSIGN, &se, ni, nj)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->f : nullptr, OP_ASSIGN, &sf, nj, nl)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->g : nullptr, OP_ASSIGN, &sg, ni, nl)) != DLA_SUCCESS) return rc;
   const size_t need = mm3_workspace_bytes(ni, nj, nl, dt);
   const bool uses_ws = (ni > 0 && nl > 0 && nj > 0);
   if (uses_ws && (!d_workspace || workspace_bytes < need || (uintptr_t)d_workspace % 256)) return DLA_ERR_WORKSPACE;

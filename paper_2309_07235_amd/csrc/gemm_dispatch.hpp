@@ -20,7 +20,7 @@ constexpr int kMaxLdsBytes = 160 * 1024;  // LDS per CU on gfx950
   X(32, 32, 16, 16)      \
   X(32, 32, 32, 32)      \
   X(64, 64, 32, 32)      \
-  X(64, 64, 64, 64)      \
+  X(64, 64, 32, 64)      \
   X(128, 64, 64, 32)     \
   X(64, 128, 32, 64)     \
   X(128, 128, 64, 64)    \

@@ -14,6 +14,7 @@
 // B (k x n) keeps n contiguous: a fragment row is one contiguous 128-byte run.
 // For the A*B^T forms the right operand is stored like A.
 #pragma once
+#include <type_traits>
 #include "dla_common.hpp"
 
 namespace dla {
@@ -54,99 +55,125 @@ struct GemmLds {
 
 // Global -> register load of a ROWS x TK tile whose k axis is contiguous in
 // memory (row r at base + r*ld).  Each thread takes pairs of k-neighbours.
+// Row pointers are set up once per tile (rows past the edge are clamped into the
+// matrix and masked), so a slab load is a handful of loads at constant offsets.
 template <typename T, int ROWS, int TK, int NT>
 struct RowTileLoader {
   static constexpr int VPR = TK / 2;
   static constexpr int TOTAL = ROWS * VPR;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
-  using vec2_t = typename Mfma<T>::vec2_t;
+  const T* p[ITER];  // element (row, 2*c2) of slab 0
+  bool ok[ITER];     // row inside the matrix
   T r[ITER][2];
 
-  __device__ inline void load_full(const T* __restrict__ base, int64_t ld, int tid) {
+  __device__ inline void init(const T* __restrict__ base, int64_t ld, int tid, int rows_valid) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int idx = tid + it * NT;
+      const int row = idx / VPR, c2 = idx % VPR;
+      const bool in = (TOTAL % NT == 0 || idx < TOTAL) && row < rows_valid;
+      ok[it] = in;
+      p[it] = base + (int64_t)(in ? row : rows_valid - 1) * ld + 2 * c2;
+    }
+  }
+  // full slab of an interior tile
+  __device__ inline void load_full(int k0) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      r[it][0] = p[it][k0];
+      r[it][1] = p[it][k0 + 1];
+    }
+  }
+  // any slab of an edge tile, or the last (partial) slab: k_valid = K - k0 >= 1.
+  // Loads stay unconditional (clamped k) and are NOT touched here: the mask is applied when the
+  // registers are written to LDS, so the loads stay in flight while the previous slab is multiplied.
+  __device__ inline void load_edge(int k0, int k_valid, int tid) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int c0 = 2 * ((tid + it * NT) % VPR), c1 = c0 + 1;
+      r[it][0] = p[it][k0 + (c0 < k_valid ? 0 : k_valid - 1 - c0)];
+      r[it][1] = p[it][k0 + (c1 < k_valid ? 1 : k_valid - 1 - c0)];
+    }
+  }
+  // MASK: zero what lies outside the matrix (edge tile or partial slab)
+  template <bool NEGATE, int STRIDE, bool MASK>
+  __device__ inline void store(T* __restrict__ s, int tid, int k_valid) const {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
       if (TOTAL % NT == 0 || idx < TOTAL) {
         const int row = idx / VPR, c2 = idx % VPR;
-        const T* p = base + (int64_t)row * ld + 2 * c2;
-        r[it][0] = p[0];
-        r[it][1] = p[1];
-      }
-    }
-  }
-  // Edge tiles: every load is issued unconditionally from an address clamped into the valid
-  // part (rows_valid, k_valid >= 1) and zeroed afterwards, so no load waits behind a branch.
-  __device__ inline void load_edge(const T* __restrict__ base, int64_t ld, int tid, int rows_valid, int k_valid) {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int idx = tid + it * NT;
-      if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int row = idx / VPR, c0 = 2 * (idx % VPR), c1 = c0 + 1;
-        const T* p = base + (int64_t)(row < rows_valid ? row : rows_valid - 1) * ld;
-        const T x0 = p[c0 < k_valid ? c0 : k_valid - 1], x1 = p[c1 < k_valid ? c1 : k_valid - 1];
-        r[it][0] = (row < rows_valid && c0 < k_valid) ? x0 : T(0);
-        r[it][1] = (row < rows_valid && c1 < k_valid) ? x1 : T(0);
-      }
-    }
-  }
-  template <bool NEGATE, int STRIDE>
-  __device__ inline void store(T* __restrict__ s, int tid) const {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int idx = tid + it * NT;
-      if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int row = idx / VPR, c2 = idx % VPR;
-        s[row * STRIDE + 2 * c2] = NEGATE ? -r[it][0] : r[it][0];
-        s[row * STRIDE + 2 * c2 + 1] = NEGATE ? -r[it][1] : r[it][1];
+        T x0 = r[it][0], x1 = r[it][1];
+        if (MASK) {
+          x0 = (ok[it] && 2 * c2 < k_valid) ? x0 : T(0);
+          x1 = (ok[it] && 2 * c2 + 1 < k_valid) ? x1 : T(0);
+        }
+        s[row * STRIDE + 2 * c2] = NEGATE ? -x0 : x0;
+        s[row * STRIDE + 2 * c2 + 1] = NEGATE ? -x1 : x1;
       }
     }
   }
 };
 
 // Global -> register load of a TK x COLS tile of a row-major k x n operand
-// (row k at base + k*ld, n contiguous).
+// (row k at base + k*ld, n contiguous).  Column offsets are clamped and masked once per tile.
 template <typename T, int TK, int COLS, int NT>
 struct ColTileLoader {
   static constexpr int VPR = COLS / 2;
   static constexpr int TOTAL = TK * VPR;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
-  using vec2_t = typename Mfma<T>::vec2_t;
+  const T* base;
+  int64_t ld;
+  int c0[ITER], c1[ITER];    // clamped column offsets
+  bool ok0[ITER], ok1[ITER];
   T r[ITER][2];
 
-  __device__ inline void load_full(const T* __restrict__ base, int64_t ld, int tid) {
+  __device__ inline void init(const T* __restrict__ b, int64_t ld_, int tid, int cols_valid) {
+    base = b;
+    ld = ld_;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int idx = tid + it * NT;
+      const int c = 2 * (idx % VPR);
+      const bool in = (TOTAL % NT == 0 || idx < TOTAL);
+      ok0[it] = in && c < cols_valid;
+      ok1[it] = in && c + 1 < cols_valid;
+      c0[it] = ok0[it] ? c : cols_valid - 1;
+      c1[it] = ok1[it] ? c + 1 : cols_valid - 1;
+    }
+  }
+  __device__ inline void load_full(int k0, int tid) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int kr = (tid + it * NT) / VPR;
+      const T* q = base + (int64_t)(k0 + kr) * ld + 2 * ((tid + it * NT) % VPR);
+      r[it][0] = q[0];
+      r[it][1] = q[1];
+    }
+  }
+  __device__ inline void load_edge(int k0, int k_valid, int tid) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int kr = (tid + it * NT) / VPR;
+      const T* q = base + (int64_t)(k0 + (kr < k_valid ? kr : k_valid - 1)) * ld;
+      r[it][0] = q[c0[it]];
+      r[it][1] = q[c1[it]];
+    }
+  }
+  template <int STRIDE, bool MASK>
+  __device__ inline void store(T* __restrict__ s, int tid, int k_valid) const {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
       if (TOTAL % NT == 0 || idx < TOTAL) {
         const int kr = idx / VPR, c2 = idx % VPR;
-        const T* p = base + (int64_t)kr * ld + 2 * c2;
-        r[it][0] = p[0];
-        r[it][1] = p[1];
-      }
-    }
-  }
-  __device__ inline void load_edge(const T* __restrict__ base, int64_t ld, int tid, int k_valid, int cols_valid) {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int idx = tid + it * NT;
-      if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int kr = idx / VPR, c0 = 2 * (idx % VPR), c1 = c0 + 1;
-        const T* p = base + (int64_t)(kr < k_valid ? kr : k_valid - 1) * ld;
-        const T x0 = p[c0 < cols_valid ? c0 : cols_valid - 1], x1 = p[c1 < cols_valid ? c1 : cols_valid - 1];
-        r[it][0] = (kr < k_valid && c0 < cols_valid) ? x0 : T(0);
-        r[it][1] = (kr < k_valid && c1 < cols_valid) ? x1 : T(0);
-      }
-    }
-  }
-  template <int STRIDE>
-  __device__ inline void store(T* __restrict__ s, int tid) const {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int idx = tid + it * NT;
-      if (TOTAL % NT == 0 || idx < TOTAL) {
-        const int kr = idx / VPR, c2 = idx % VPR;
-        s[kr * STRIDE + 2 * c2] = r[it][0];
-        s[kr * STRIDE + 2 * c2 + 1] = r[it][1];
+        T x0 = r[it][0], x1 = r[it][1];
+        if (MASK) {
+          x0 = (ok0[it] && kr < k_valid) ? x0 : T(0);
+          x1 = (ok1[it] && kr < k_valid) ? x1 : T(0);
+        }
+        s[kr * STRIDE + 2 * c2] = x0;
+        s[kr * STRIDE + 2 * c2 + 1] = x1;
       }
     }
   }
@@ -238,55 +265,73 @@ gemm_kernel(const GemmGroup<T> g) {
   const T* const Bg = BT ? P.B + (int64_t)n0 * ldb : P.B + n0;
   const int nslab = (K + TK - 1) / TK;
 
-  auto fetch = [&](int s) {
+  la.init(Ag, lda, tid, M - m0);
+  if (BT) lbt.init(Bg, ldb, tid, N - n0);
+  else lbn.init(Bg, ldb, tid, N - n0);
+  // Two copies of the pipeline, chosen per slab: interior slabs (whole tile inside the matrix, whole
+  // slab inside K) load at constant offsets and store unmasked; everything else takes the clamped
+  // loads and the masked store.  Kept as separate loops so that the fast one stays free of selects.
+  auto fetch = [&](auto edge, int s) {
     const int k0 = s * TK;
-    const bool full = full_mn && (k0 + TK <= K);
-    if (full) {
-      la.load_full(Ag + k0, lda, tid);
-      if (BT) lbt.load_full(Bg + k0, ldb, tid);
-      else lbn.load_full(Bg + (int64_t)k0 * ldb, ldb, tid);
+    if constexpr (!decltype(edge)::value) {
+      la.load_full(k0);
+      if (BT) lbt.load_full(k0);
+      else lbn.load_full(k0, tid);
     } else {
-      la.load_edge(Ag + k0, lda, tid, M - m0, K - k0);
-      if (BT) lbt.load_edge(Bg + k0, ldb, tid, N - n0, K - k0);
-      else lbn.load_edge(Bg + (int64_t)k0 * ldb, ldb, tid, K - k0, N - n0);
+      la.load_edge(k0, K - k0, tid);
+      if (BT) lbt.load_edge(k0, K - k0, tid);
+      else lbn.load_edge(k0, K - k0, tid);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](auto edge, int buf, int s) {  // s: the slab that sits in the registers
+    constexpr bool E = decltype(edge)::value;
     T* sa = smem + buf * L::STAGE;
     T* sb = sa + L::A_PAD;
-    la.template store<SUB, L::SA>(sa, tid);  // subtracting forms multiply by -A
-    if (BT) lbt.template store<false, L::SB>(sb, tid);
-    else lbn.template store<L::SB>(sb, tid);
+    const int kv = K - s * TK;
+    la.template store<SUB, L::SA, E>(sa, tid, kv);  // subtracting forms multiply by -A
+    if (BT) lbt.template store<false, L::SB, E>(sb, tid, kv);
+    else lbn.template store<L::SB, E>(sb, tid, kv);
   };
+  // iterations [s0, s1): multiply slab s while slab s + 1 (when there is one) is fetched in mode `edge`
+  auto slabs = [&](auto edge, int s0, int s1) {
+    for (int s = s0; s < s1; ++s) {
+      const bool more = !decltype(edge)::value || (s + 1 < nslab);
+      if (more) fetch(edge, s + 1);
+      const T* sa = smem + (s & 1) * L::STAGE;
+      const T* sb = sa + L::A_PAD;
+      const T* pa = sa + (wm0 + l15) * L::SA + l4;
+      const T* pb = BT ? sb + (wn0 + l15) * L::SB + l4 : sb + l4 * L::SB + wn0 + l15;
+#pragma unroll UK
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        T fa[FM], fb[FN];
+#pragma unroll
+        for (int a = 0; a < FM; ++a) fa[a] = pa[a * 16 * L::SA + kk * 4];
+#pragma unroll
+        for (int b = 0; b < FN; ++b) fb[b] = BT ? pb[b * 16 * L::SB + kk * 4] : pb[kk * 4 * L::SB + b * 16];
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+          for (int b = 0; b < FN; ++b) acc[a][b] = Mfma<T>::mma(fa[a], fb[b], acc[a][b]);
+      }
+      if (more) stash(edge, (s + 1) & 1, s + 1);
+      lds_barrier();
+    }
+  };
+  using interior_t = std::integral_constant<bool, false>;
+  using edge_t = std::integral_constant<bool, true>;
+  const int nfull = full_mn ? K / TK : 0;  // leading slabs that need no mask
 
-  if (nslab > 0) {
-    fetch(0);
-    stash(0);
+  if (nfull > 0) {
+    fetch(interior_t{}, 0);
+    stash(interior_t{}, 0, 0);
+  } else if (nslab > 0) {
+    fetch(edge_t{}, 0);
+    stash(edge_t{}, 0, 0);
   }
   lds_barrier();
-
-  for (int s = 0; s < nslab; ++s) {
-    const bool more = (s + 1 < nslab);
-    if (more) fetch(s + 1);
-    const T* sa = smem + (s & 1) * L::STAGE;
-    const T* sb = sa + L::A_PAD;
-    const T* pa = sa + (wm0 + l15) * L::SA + l4;
-    const T* pb = BT ? sb + (wn0 + l15) * L::SB + l4 : sb + l4 * L::SB + wn0 + l15;
-#pragma unroll UK
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-      T fa[FM], fb[FN];
-#pragma unroll
-      for (int a = 0; a < FM; ++a) fa[a] = pa[a * 16 * L::SA + kk * 4];
-#pragma unroll
-      for (int b = 0; b < FN; ++b) fb[b] = BT ? pb[b * 16 * L::SB + kk * 4] : pb[kk * 4 * L::SB + b * 16];
-#pragma unroll
-      for (int a = 0; a < FM; ++a)
-#pragma unroll
-        for (int b = 0; b < FN; ++b) acc[a][b] = Mfma<T>::mma(fa[a], fb[b], acc[a][b]);
-    }
-    if (more) stash((s + 1) & 1);
-    lds_barrier();
-  }
+  const int split = nfull > 0 ? nfull - 1 : 0;  // iterations below it prefetch an interior slab
+  slabs(interior_t{}, 0, split);
+  slabs(edge_t{}, split, nslab);
 
   // ---- store ---------------------------------------------------------------------
 #pragma unroll

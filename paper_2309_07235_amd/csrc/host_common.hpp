@@ -12,7 +12,9 @@ enum Phase { PHASE_GEMM = 0, PHASE_DIAG = 1, PHASE_TRSM = 2, PHASE_COUNT = 3 };
 
 // Fills defaults into a user schedule and checks it against the menu.
 // op selects which LDS layout the fit check uses.
-int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out);
+// m, n (optional): the output size, used to pick the default macro-tile when the caller names none.
+int resolve_schedule(dla_dtype dt, const dla_gemm_params* in, int op, GemmSchedule* out, int64_t m = 0,
+                     int64_t n = 0);
 
 template <typename T>
 inline GemmProblem<T> make_problem(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B, int64_t ldb,
