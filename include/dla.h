@@ -61,7 +61,7 @@ enum { DLA_KERNEL_MM3 = 0, DLA_KERNEL_LU = 1, DLA_KERNEL_CHOLESKY = 2 };
  */
 typedef struct {
   int tile_m, tile_n; /* workgroup macro-tile, multiples of 16                                 */
-  int tile_k;         /* depth of the k-slab staged in LDS per main-loop iteration (8/16/32)    */
+  int tile_k;         /* depth of the k-slab staged in LDS per main-loop iteration (8/16/32/128) */
   int unroll_k;       /* 16x16x4 MFMA k-steps unrolled together inside a slab (1, 2, 4, 8)      */
   int wave_m, wave_n; /* sub-tile one 64-lane wavefront accumulates in registers                */
 } dla_gemm_params;

@@ -124,7 +124,7 @@ int run_gemm(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B,
   GemmGroup<T> g;
   g.nprob = 1;
   g.prob[0] = make_problem<T>(s, op, A, lda, B, ldb, C, ldc, M, N, K, 0);
-  g.prob[1] = g.prob[0];
+  for (int q = 1; q < kMaxGroup; ++q) g.prob[q] = g.prob[0];
   g.total_tiles = problem_tiles(s, op, g.prob[0]);
   const double flops = (op == OP_SUB_NT_LOWER ? 1.0 : 2.0) * (double)M * (double)N * (double)K;
   ProfileScope scope(PHASE_GEMM, flops, st);
@@ -189,6 +189,7 @@ static int mm3_impl(const T* A, int64_t lda, const T* B, int64_t ldb, const T* C
     const int t0 = problem_tiles(se, OP_ASSIGN, g.prob[0]);
     g.prob[1] = make_problem<T>(se, OP_ASSIGN, C, ldc, D, ldd, F, L.ldf, nj, nl, nm, t0);
     g.total_tiles = t0 + problem_tiles(se, OP_ASSIGN, g.prob[1]);
+    g.prob[2] = g.prob[1];
     ProfileScope scope(PHASE_GEMM, 2.0 * ((double)ni * nj * nk + (double)nj * nl * nm), st);
     if ((rc = launch_gemm<T>(se, OP_ASSIGN, g, st)) != DLA_SUCCESS) return rc;
   } else {

@@ -2,6 +2,7 @@
 // register layouts of the 16x16x4 matrix instructions on gfx950.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace dla {

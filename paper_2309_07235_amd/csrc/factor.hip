@@ -3,9 +3,13 @@
 // trailing matrix with the MFMA GEMM (the step that dominates the run time).
 #include "factor_kernels.hpp"
 #include "update_kernel.hpp"
+#include "head_kernel.hpp"
 #include "host_common.hpp"
 
 namespace dla {
+
+constexpr int kNumCu = 256;   // compute units of an MI355X
+constexpr int kChainCu = 32;  // left to the latency chain while a bulk update runs
 
 static inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -34,6 +38,14 @@ int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, 
   return resolve_schedule(dt, in ? &in->update : nullptr, op, upd);
 }
 
+// Launch with an optional completion event: the event rides on the kernel's own dispatch packet
+// instead of a separate marker packet behind it, which shortens the hand-over to a waiting stream.
+template <typename K, typename A>
+static inline void launch_ev(K kern, dim3 grid, dim3 block, int lds, hipStream_t st, hipEvent_t done, const A& a) {
+  if (done) hipExtLaunchKernelGGL(kern, grid, block, lds, st, nullptr, done, 0, a);
+  else hipLaunchKernelGGL(kern, grid, block, lds, st, a);
+}
+
 template <typename T, int KIND>
 static int launch_diag(const DiagArgs<T>& a, hipStream_t st) {
   auto kern = diag_kernel<T, KIND>;
@@ -51,7 +63,8 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st) {
 
 // Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp).
 template <typename T, int KIND>
-static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, hipStream_t st) {
+static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
+                         hipStream_t st, hipEvent_t done = nullptr) {
   if (m <= 0) return DLA_SUCCESS;
   constexpr bool LOWER = (KIND == KIND_CHOL);
   auto kern = update_kernel<T, LOWER>;
@@ -70,11 +83,11 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
   a.ld = ld;
   a.m = (int)m;
   a.b = b;
+  a.skip = skip;
   const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
   int64_t total_blocks = 0;
   for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)m, LOWER);
-  // one 8-wave workgroup per compute unit: aim at one full round of at most 256 items
-  const int slots = 256;
+  // one 8-wave workgroup fits per compute unit: aim at one round of at most `slots` items
   a.bpi = (int)((total_blocks + slots - 1) / slots);
   if (a.bpi < 1) a.bpi = 1;
   int items = 0;
@@ -85,14 +98,14 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
   a.items = items;
-  const double flops = (LOWER ? 1.0 : 2.0) * (double)m * (double)m * (double)b;
+  const double flops = (LOWER ? 1.0 : 2.0) * ((double)m * (double)m - (double)skip * (double)skip) * (double)b;
   ProfileScope scope(PHASE_GEMM, flops, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, a);
+  launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
 template <typename T, int KIND>
-static int launch_trsm(TrsmArgs<T> a, hipStream_t st) {
+static int launch_trsm(TrsmArgs<T> a, hipStream_t st, hipEvent_t done = nullptr) {
   auto kern = trsm_kernel<T, KIND>;
   static bool attr_done = false;
   if (!attr_done) {
@@ -107,30 +120,56 @@ static int launch_trsm(TrsmArgs<T> a, hipStream_t st) {
   const int grid = a.n_left + wgs;
   if (grid <= 0) return DLA_SUCCESS;
   ProfileScope scope(PHASE_TRSM, 0.0, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kTrsmThreads), trsm_lds_bytes<T>(), st, a);
+  launch_ev(kern, dim3((unsigned)grid), dim3(kTrsmThreads), trsm_lds_bytes<T>(), st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
-// Helper stream and events for look-ahead: library-owned, default priority, created on first use
+template <typename T, int KIND>
+static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done = nullptr) {
+  auto kern = head_kernel<T, KIND>;
+  constexpr int lds = head_lds_bytes<T, KIND>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+        hipSuccess)
+      return DLA_ERR_HIP;
+    attr_done = true;
+  }
+  const int nt = (a.bn + kHeadTile - 1) / kHeadTile;
+  const int grid = (KIND == KIND_LU) ? nt * nt : nt * (nt + 1) / 2;
+  ProfileScope scope(PHASE_TRSM, 0.0, st);
+  launch_ev(kern, dim3((unsigned)grid), dim3(kHeadThreads), lds, st, done, a);
+  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+}
+
+// Helper streams and events for look-ahead: library-owned, default priority, created on first use
 // and kept for the life of the process.
 struct LookaheadCtx {
-  hipStream_t helper = nullptr;
+  hipStream_t panel = nullptr;  // panel solves + strip updates
+  hipStream_t bulk = nullptr;   // bulk trailing updates
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ok = false;
 };
 static LookaheadCtx& lookahead_ctx() {
   static LookaheadCtx ctx;
   if (!ctx.ok) {
-    bool good = hipStreamCreateWithFlags(&ctx.helper, hipStreamNonBlocking) == hipSuccess;
+    bool good = hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
+                hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; i < 4 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
     ctx.ok = good;
   }
   return ctx;
 }
 
-// Schedule of the small look-ahead panel updates (skinny products with k = nb): small tiles, so a
-// panel that is only a few hundred rows long still spreads over many compute units.
-static GemmSchedule panel_schedule() { return GemmSchedule{32, 32, 16, 4, 16, 16}; }
+// Schedule of the small strip updates (skinny products with k = nb): small tiles, so a panel
+// that is only a few hundred rows long still spreads over many compute units, and the whole k
+// extent in one slab, so a tile costs one round of global loads instead of one per slab (these
+// launches sit on the latency chain and run beside a bulk update that keeps the memory busy).
+// That variant needs a compute unit's registers to itself, so it is used once the bulk update has
+// become small (late steps); beside a large bulk update the 16-deep slabs share compute units better.
+static GemmSchedule panel_schedule(int64_t mr) {
+  return mr <= 2304 ? GemmSchedule{32, 32, 128, 8, 16, 16} : GemmSchedule{32, 32, 16, 4, 16, 16};
+}
 
 template <typename T, int KIND>
 static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
@@ -150,21 +189,23 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   auto inv_lo_of = [&](int step) { return reinterpret_cast<T*>(wsb + (size_t)(2 * (step & 1)) * set); };
   auto inv_up_of = [&](int step) { return reinterpret_cast<T*>(wsb + (size_t)(2 * (step & 1) + 1) * set); };
 
-  // diagonal block + panel solves of the block column starting at k0, on stream s
-  auto panel = [&](int64_t k0, int step, hipStream_t s) -> int {
-    const int b = (int)((n - k0 < nb) ? n - k0 : nb);
-    const int64_t m = n - k0 - b;
-    T* const Akk = A + k0 * lda + k0;
+  auto diag = [&](int64_t k0, int step, hipStream_t s) -> int {
     DiagArgs<T> da;
-    da.A = Akk;
+    da.A = A + k0 * lda + k0;
     da.lda = lda;
-    da.b = b;
+    da.b = (int)((n - k0 < nb) ? n - k0 : nb);
     da.k0 = (int)k0;
     da.info = d_info;
     da.inv_lo = inv_lo_of(step);
     da.inv_up = inv_up_of(step);
-    int r = launch_diag<T, KIND>(da, s);
-    if (r != DLA_SUCCESS || m == 0) return r;
+    return launch_diag<T, KIND>(da, s);
+  };
+  // panel solves of the block column / block row behind diagonal block k0
+  auto solves = [&](int64_t k0, int step, hipStream_t s, hipEvent_t done) -> int {
+    const int b = (int)((n - k0 < nb) ? n - k0 : nb);
+    const int64_t m = n - k0 - b;
+    if (m == 0) return DLA_SUCCESS;
+    T* const Akk = A + k0 * lda + k0;
     TrsmArgs<T> ta;
     ta.D = Akk;
     ta.left = Akk + b;                  // A12: b x m
@@ -173,97 +214,157 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     ta.b = b;
     ta.m = (int)m;
     ta.n_left = 0;
-    ta.inv_lo = da.inv_lo;
-    ta.inv_up = da.inv_up;
-    return launch_trsm<T, KIND>(ta, s);
+    ta.inv_lo = inv_lo_of(step);
+    ta.inv_up = inv_up_of(step);
+    return launch_trsm<T, KIND>(ta, s, done);
   };
-  // trailing-update schedule for an m x m update: the caller's, or by default small macro-tiles.
-  // With k = nb the update streams the trailing matrix once (16 flop per byte at nb = 128), so
-  // what matters is how well loads, MFMA and stores of many co-resident workgroups overlap;
-  // measured on the update shape, 64 x 64 tiles win for large m and 32 x 32 below that.
-  auto update_schedule = [&](int64_t m) {
-    if (!auto_tile) return upd;
-    GemmSchedule s = upd;
-    if (KIND == KIND_LU && m >= 3000) {
-      s.tm = s.tn = 64;
-      s.wm = s.wn = 32;
-    } else {
-      s.tm = s.tn = 32;
-      s.wm = s.wn = 16;
-    }
-    return s;
-  };
+  // trailing-update schedule for an m x m update when the caller names the tile
+  auto update_schedule = [&](int64_t) { return upd; };
 
-  // m x m trailing update behind the panel whose L21 / U12 are given
-  auto trailing = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, hipStream_t s) -> int {
-    if (auto_tile) return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, s);
+  // mm x mm trailing update behind the panel whose L21 / U12 are given.  skip > 0: the leading
+  // skip x skip block of the region is left alone (another stream owns it).
+  // In the look-ahead pipeline the bulk update leaves a few compute units free: its workgroups fill
+  // a compute unit's registers, so the small kernels of the latency chain (diagonal block, head
+  // update) would otherwise queue behind a whole bulk update.
+  const bool pipelined = lookahead && n > 2 * (int64_t)nb;
+  const int slots = pipelined ? kNumCu - kChainCu : kNumCu;
+  auto trailing_gemm = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, int skip, hipStream_t s) -> int {
     const GemmSchedule us = update_schedule(mm);
-    if (KIND == KIND_LU) return run_gemm<T>(us, OP_SUB, Lp, lda, Up, lda, Cp, lda, mm, mm, bb, s);
-    return run_gemm<T>(us, OP_SUB_NT_LOWER, Lp, lda, Lp, lda, Cp, lda, mm, mm, bb, s);
+    if (skip == 0) {
+      if (KIND == KIND_LU) return run_gemm<T>(us, OP_SUB, Lp, lda, Up, lda, Cp, lda, mm, mm, bb, s);
+      return run_gemm<T>(us, OP_SUB_NT_LOWER, Lp, lda, Lp, lda, Cp, lda, mm, mm, bb, s);
+    }
+    // region minus its leading block: the rows below the block over the full width, and (LU) the
+    // block's rows to the right of it
+    const int64_t rest = mm - skip;
+    if (rest <= 0) return DLA_SUCCESS;
+    int r;
+    if (KIND == KIND_LU) {
+      if ((r = run_gemm<T>(us, OP_SUB, Lp, lda, Up + skip, lda, Cp + skip, lda, skip, rest, bb, s)) != DLA_SUCCESS) return r;
+      return run_gemm<T>(us, OP_SUB, Lp + (int64_t)skip * lda, lda, Up, lda, Cp + (int64_t)skip * lda, lda, rest, mm, bb, s);
+    }
+    const T* Lr = Lp + (int64_t)skip * lda;
+    if ((r = run_gemm<T>(us, OP_SUB_NT, Lr, lda, Lp, lda, Cp + (int64_t)skip * lda, lda, rest, skip, bb, s)) != DLA_SUCCESS)
+      return r;
+    return run_gemm<T>(us, OP_SUB_NT_LOWER, Lr, lda, Lr, lda, Cp + (int64_t)skip * lda + skip, lda, rest, rest, bb, s);
+  };
+  // done (optional): event that completes with the update
+  auto trailing = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, int skip, hipStream_t s,
+                      hipEvent_t done) -> int {
+    if (auto_tile) return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, skip, slots, s, done);
+    const int r = trailing_gemm(Lp, Up, Cp, mm, bb, skip, s);
+    if (r != DLA_SUCCESS) return r;
+    if (done && hipEventRecord(done, s) != hipSuccess) return DLA_ERR_HIP;
+    return DLA_SUCCESS;
   };
 
-  LookaheadCtx* ctx = nullptr;
-  if (lookahead && n > 2 * (int64_t)nb) {
-    ctx = &lookahead_ctx();
-    if (!ctx->ok) return DLA_ERR_HIP;
-  }
-
-  // Look-ahead keeps the latency chain  diag(k) -> panel solves(k) -> strip update(k) -> diag(k+1)
-  // back to back on the caller's stream; the bulk of every trailing update runs on the helper
-  // stream.  "Strip k+1" is what the next panel needs: the next block column and block row of
-  // the trailing matrix.  bulk(k) updates everything behind strip k+1 and may still be running
-  // while panel k+1 is factored.  strip(k+1) touches memory bulk(k) writes, so it waits for it.
-  hipEvent_t e_panel = ctx ? ctx->ev[0] : nullptr;  // recorded on the caller's stream after the panel solves
-  hipEvent_t e_bulk = ctx ? ctx->ev[1] : nullptr;   // recorded on the helper stream after a bulk update
-  bool bulk_pending = false;
-
-  if ((rc = panel(0, 0, st)) != DLA_SUCCESS) return rc;
-  int step = 0;
-  for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
-    const int b = (int)((n - k0 < nb) ? n - k0 : nb);
-    const int64_t m = n - k0 - b;
-    if (m == 0) break;
-    T* const Akk = A + k0 * lda + k0;
-    T* const L21 = Akk + (int64_t)b * lda;  // m x b
-    T* const U12 = Akk + b;                 // b x m   (LU)
-    T* const A22 = L21 + b;
-    const int64_t bn = m < nb ? m : nb;      // width of the next block column
-    const int64_t mr = m - bn;               // what is left behind it
-    if (ctx && mr > 0) {
-      // bulk(k) on the helper stream: needs panel k (event) and, through stream order, bulk(k-1)
-      if (hipEventRecord(e_panel, st) != hipSuccess || hipStreamWaitEvent(ctx->helper, e_panel, 0) != hipSuccess)
-        return DLA_ERR_HIP;
-      // strip(k) on the caller's stream: needs bulk(k-1), which wrote the same strip
-      if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
-      const GemmSchedule ps = panel_schedule();
-      if (KIND == KIND_LU) {
-        GemmGroup<T> g;
-        g.nprob = 2;
-        g.prob[0] = make_problem<T>(ps, OP_SUB, L21, lda, U12, lda, A22, lda, m, bn, b, 0);  // block column
-        const int t0 = problem_tiles(ps, OP_SUB, g.prob[0]);
-        g.prob[1] = make_problem<T>(ps, OP_SUB, L21, lda, U12 + bn, lda, A22 + bn, lda, bn, mr, b, t0);  // block row
-        g.total_tiles = t0 + problem_tiles(ps, OP_SUB, g.prob[1]);
-        ProfileScope scope(PHASE_GEMM, 2.0 * (double)b * ((double)m * bn + (double)bn * mr), st);
-        if ((rc = launch_gemm<T>(ps, OP_SUB, g, st)) != DLA_SUCCESS) return rc;
-      } else {
-        if ((rc = run_gemm<T>(ps, OP_SUB_NT, L21, lda, L21, lda, A22, lda, m, bn, b, st)) != DLA_SUCCESS) return rc;
-      }
-      T* const C = A22 + bn * lda + bn;
-      if ((rc = trailing(L21 + bn * lda, U12 + bn, C, mr, b, ctx->helper)) != DLA_SUCCESS) return rc;
-      if (hipEventRecord(e_bulk, ctx->helper) != hipSuccess) return DLA_ERR_HIP;
-      bulk_pending = true;
-      // next panel right behind the strip update, on the caller's stream
-      if ((rc = panel(k0 + b, step + 1, st)) != DLA_SUCCESS) return rc;
-    } else {
-      if (bulk_pending) {  // join: the remaining steps run on the caller's stream only
-        if (hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
-        bulk_pending = false;
-      }
-      if ((rc = trailing(L21, U12, A22, m, b, st)) != DLA_SUCCESS) return rc;
-      if ((rc = panel(k0 + b, step + 1, st)) != DLA_SUCCESS) return rc;
+  if (!pipelined) {
+    // one stream, strictly sequential steps
+    int step = 0;
+    for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
+      const int b = (int)((n - k0 < nb) ? n - k0 : nb);
+      const int64_t m = n - k0 - b;
+      if ((rc = diag(k0, step, st)) != DLA_SUCCESS) return rc;
+      if (m == 0) break;
+      if ((rc = solves(k0, step, st, nullptr)) != DLA_SUCCESS) return rc;
+      T* const Akk = A + k0 * lda + k0;
+      if ((rc = trailing(Akk + (int64_t)b * lda, Akk + b, Akk + (int64_t)b * lda + b, m, b, 0, st, nullptr)) != DLA_SUCCESS) return rc;
     }
+  } else {
+    // Look-ahead pipeline over three streams.  With N = block k+1 and N2 = block k+2:
+    //   caller's stream   diag(k) -> head(k): block (N,N) gets step k's update from the un-solved panel
+    //                     heads -> diag(k+1) -> ...        (the latency chain, nothing else on it)
+    //   panel stream      solves(k): the full panel solves;  strips(k): step k's update of block
+    //                     row N and block column N (what solves(k+1) reads) and of block (N2,N2)
+    //                     (what head(k+1) reads)
+    //   bulk stream       bulk(k): step k's update of everything behind block row/column N except
+    //                     block (N2,N2)
+    // Dependencies beyond stream order: head(k) after strips(k-1); solves(k) after head(k) (it
+    // overwrites the panel heads head(k) reads); strips(k) after bulk(k-1) (same memory);
+    // bulk(k) after solves(k).
+    LookaheadCtx& ctx = lookahead_ctx();
+    if (!ctx.ok) return DLA_ERR_HIP;
+    hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_strip = ctx.ev[2], e_bulk = ctx.ev[3];
+    bool strip_pending = false, bulk_pending = false;
+    constexpr int SOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT;
+
+    if ((rc = diag(0, 0, st)) != DLA_SUCCESS) return rc;
+    int step = 0;
+    for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
+      const int b = (int)((n - k0 < nb) ? n - k0 : nb);
+      const int64_t m = n - k0 - b;
+      if (m == 0) break;
+      T* const Akk = A + k0 * lda + k0;
+      T* const L21 = Akk + (int64_t)b * lda;  // m x b
+      T* const U12 = Akk + b;                 // b x m   (LU)
+      T* const A22 = L21 + b;
+      const int64_t bn = m < nb ? m : nb;       // size of block N
+      const int64_t mr = m - bn;                // what is left behind it
+      const int64_t bn2 = mr < nb ? mr : nb;    // size of block N2
+
+      // ---- caller's stream: head(k), diag(k+1)
+      if (strip_pending && hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
+      HeadArgs<T> ha;
+      ha.D = Akk;
+      ha.top = U12;
+      ha.side = L21;
+      ha.C = A22;
+      ha.lda = lda;
+      ha.b = b;
+      ha.bn = (int)bn;
+      ha.inv_lo = inv_lo_of(step);
+      ha.inv_up = inv_up_of(step);
+      if ((rc = launch_head<T, KIND>(ha, st, e_head)) != DLA_SUCCESS) return rc;
+      if ((rc = diag(k0 + b, step + 1, st)) != DLA_SUCCESS) return rc;
+
+      // ---- panel stream: solves(k), strips(k)
+      if (hipStreamWaitEvent(ctx.panel, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
+      // the last kernel of the step on this stream carries e_strip
+      if ((rc = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return rc;
+      if (mr > 0) {
+        if (bulk_pending && hipStreamWaitEvent(ctx.panel, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
+        const T* Lr = L21 + bn * lda;  // rows behind block N of the solved column panel
+        const GemmSchedule ps = panel_schedule(mr);
+        GemmGroup<T> g;
+        int np = 0, tiles = 0;
+        double flops = 0.0;
+        auto add = [&](const T* a, const T* bm, T* c, int64_t M, int64_t N) {
+          g.prob[np] = make_problem<T>(ps, SOP, a, lda, bm, lda, c, lda, M, N, b, tiles);
+          tiles += problem_tiles(ps, SOP, g.prob[np]);
+          flops += 2.0 * (double)M * (double)N * (double)b;
+          ++np;
+        };
+        if (KIND == KIND_LU) {
+          add(Lr, U12, A22 + bn * lda, mr, bn);                   // block column N below block (N,N)
+          add(L21, U12 + bn, A22 + bn, bn, mr);                   // block row N right of block (N,N)
+          add(Lr, U12 + bn, A22 + bn * lda + bn, bn2, bn2);       // block (N2,N2)
+        } else {
+          add(Lr, L21, A22 + bn * lda, mr, bn);                   // block column N below block (N,N)
+          add(Lr, Lr, A22 + bn * lda + bn, bn2, bn2);             // block (N2,N2)
+        }
+        for (int q = np; q < kMaxGroup; ++q) g.prob[q] = g.prob[0];
+        g.nprob = np;
+        g.total_tiles = tiles;
+        {
+          ProfileScope scope(PHASE_GEMM, flops, ctx.panel);
+          tl_gemm_done_event = e_strip;
+          if ((rc = launch_gemm<T>(ps, SOP, g, ctx.panel)) != DLA_SUCCESS) return rc;
+        }
+      }
+      strip_pending = true;
+
+      // ---- bulk stream: bulk(k)
+      if (mr > bn2) {
+        if (hipStreamWaitEvent(ctx.bulk, e_solve, 0) != hipSuccess) return DLA_ERR_HIP;
+        if ((rc = trailing(L21 + bn * lda, U12 + bn, A22 + bn * lda + bn, mr, b, (int)bn2, ctx.bulk, e_bulk)) != DLA_SUCCESS)
+          return rc;
+        bulk_pending = true;
+      }
+    }
+    // join: everything the helper streams did becomes part of the caller's stream
+    if (strip_pending && hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
+    if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
   }
-  if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
   if (KIND == KIND_CHOL && n > 1) {
     hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),
                        dim3(256), 0, st, A, lda, (int)n);

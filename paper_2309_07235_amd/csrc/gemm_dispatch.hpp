@@ -29,7 +29,11 @@ constexpr int kMaxLdsBytes = 160 * 1024;  // LDS per CU on gfx950
   X(128, 256, 64, 64)
 
 // k-slab depths and unroll factors instantiated for every macro-tile: X(TK, UK)
-#define DLA_KU_MENU(X) X(8, 1) X(8, 2) X(16, 1) X(16, 2) X(16, 4) X(32, 2) X(32, 4) X(32, 8)
+#define DLA_KU_MENU(X) X(8, 1) X(8, 2) X(16, 1) X(16, 2) X(16, 4) X(32, 2) X(32, 4) X(32, 8) X(128, 8)
+
+// Completion event for the NEXT GEMM launch of this host thread (consumed and cleared by that
+// launch): it rides on the kernel's dispatch packet instead of a marker packet behind it.
+inline thread_local hipEvent_t tl_gemm_done_event = nullptr;
 
 template <typename T, int TM, int TN, int WM, int WN>
 int launch_gemm_tile(const GemmSchedule& s, int op, const GemmGroup<T>& g, hipStream_t st);

@@ -32,9 +32,11 @@ struct GemmProblem {
   int tile_begin;  // first logical tile id of this problem inside the group
 };
 
+constexpr int kMaxGroup = 3;  // products one launch can carry
+
 template <typename T>
 struct GemmGroup {
-  GemmProblem<T> prob[2];
+  GemmProblem<T> prob[kMaxGroup];
   int nprob;
   int total_tiles;
 };
@@ -199,7 +201,10 @@ gemm_kernel(const GemmGroup<T> g) {
 
   // ---- which tile ----------------------------------------------------------------
   const int logical = xcd_contiguous_id((int)blockIdx.x, g.total_tiles);
-  const int pi = (g.nprob > 1 && logical >= g.prob[1].tile_begin) ? 1 : 0;
+  int pi = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxGroup; ++q)
+    if (q < g.nprob && logical >= g.prob[q].tile_begin) pi = q;
   const GemmProblem<T>& P = g.prob[pi];
   const int local = logical - P.tile_begin;
   int ti, tj;

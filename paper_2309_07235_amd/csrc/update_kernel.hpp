@@ -43,6 +43,7 @@ struct UpdateArgs {
   int m, b;
   int bpi;      // target number of 32-column blocks per work item
   int items;    // number of work items = grid size
+  int skip;     // the leading skip x skip block of C (skip: multiple of 16) is not written: another stream owns it
 };
 
 template <typename T, bool LOWER>
@@ -226,12 +227,14 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
 #endif
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
+    for (int q = 0; q < 2; ++q) {
+      if (wrow0 < g.skip && j0 + q * 16 < g.skip) continue;  // uniform per wave: the excluded leading block
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
         if (full || (wrow0 + r < m && cc < m)) Cw[(int64_t)r * ld + cc] = c[q][v];
       }
+    }
   };
   auto multiply = [&](acc_t (&c)[2], int buf) {
     const T* sb = smem + buf * LD::B_PAD + lane;
