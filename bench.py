@@ -4,9 +4,9 @@
 A step is one pass over the whole hot path on one batch of seeded synthetic
 input resident in HBM: lu_factor (N=4000), cholesky_factor (N=4000) and mm3
 (extralarge rectangular shape).  Prints ONE JSON line with the whole-job
-throughput in fp64 GFLOP/s, the roofline of the dominant kernel (the MFMA GEMM
-behind the trailing updates and the 3mm products, timed per launch with HIP
-events on its own stream) and the CPU oracle timed on the host cores.
+throughput in fp64 GFLOP/s, the roofline of the dominant kernel (the rank-128
+trailing update of the two factorisations, timed per launch with HIP events on
+the stream it runs on) and the CPU oracle timed on the host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
 """
@@ -24,6 +24,34 @@ sys.path.insert(0, ROOT)
 N_FACTOR = 4000
 PEAK_F64_MFMA_TFLOPS = 78.6   # MI355X published dense fp64 matrix peak
 METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
+# HBM bytes per launch of the bulk update kernel (fetch + write), from the two rocprofv3 --pmc passes
+# summarised in profiles/update_kernel_hbm_traffic_n4000.txt (counter readings scaled by the same
+# counters' readings for a device copy of known size).  None until measured.
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74550 * 1024
+
+
+def update_algorithmic_bytes(n, nb=128, lower=False):
+    """(launches, bytes) the bulk updates of one factorisation must move: every element of the region
+    read and written once, the two panels read once (blocks of 128 rows for the lower-triangular case)."""
+    launches, total = 0, 0
+    k0 = 0
+    while True:
+        m = n - k0 - nb
+        if m <= 0:
+            break
+        bn = min(nb, m)
+        mr = m - bn
+        bn2 = min(nb, mr)
+        if mr > bn2:
+            if lower:
+                elems = sum(min(128, mr - r0) * min(r0 + 128, mr) for r0 in range(0, mr, 128))
+            else:
+                elems = mr * mr
+            elems -= bn2 * bn2
+            total += 8 * (2 * elems + (1 if lower else 2) * mr * nb)
+            launches += 1
+        k0 += nb
+    return launches, total
 
 
 def lu_flops(n):
@@ -120,11 +148,18 @@ def main() -> int:
         torch.cuda.synchronize()
 
     kernels = {}
-    gemm_ms = gemm_fl = 0.0
-    gemm_launches = 0
+    upd_ms = upd_fl = 0.0
+    upd_launches = 0
     runs = (("lu", lambda r: B.lu_factor(lu_bufs[r], p_lu, workspace=ws_f), lu_flops(n), lu_bufs, d_lu0),
             ("cholesky", lambda r: B.cholesky_factor(ch_bufs[r], p_ch, workspace=ws_f), chol_flops(n), ch_bufs, d_ch0),
             ("mm3", lambda r: B.mm3(*d_ops, d_g, p_mm, workspace=ws_m), mm3_flops(dims), None, None))
+
+    def phase(ph, reps):
+        ms, cnt, pf = B.profile_read(ph)
+        return {"launches_per_call": cnt // reps, "ms_per_call": round(ms / reps, 4),
+                "avg_launch_us": round(ms / cnt * 1e3, 2) if cnt else None,
+                "tflops": round(pf / ms * 1e-9, 2) if ms > 0 and pf > 0 else None}, ms, cnt, pf
+
     for name, fn, fl, bufs, src in runs:
         reps = min(K, total)
         if bufs is not None:
@@ -135,21 +170,22 @@ def main() -> int:
         B.profile_enable(True)
         timed(fn, reps)
         B.profile_enable(False)
-        ms, cnt, pf = B.profile_read(B.PHASE_GEMM)
-        dms, dcnt, _ = B.profile_read(B.PHASE_DIAG)
-        tms, tcnt, _ = B.profile_read(B.PHASE_TRSM)
+        gemm, _, _, _ = phase(B.PHASE_GEMM, reps)
+        diag, _, _, _ = phase(B.PHASE_DIAG, reps)
+        solve, _, _, _ = phase(B.PHASE_TRSM, reps)
+        upd, ums, ucnt, ufl = phase(B.PHASE_UPDATE, reps)
         kernels[name] = {
             "ms": round(sec * 1e3, 4), "gflops": round(fl / sec * 1e-9, 1),
             "pct_of_peak": round(fl / sec * 1e-12 / PEAK_F64_MFMA_TFLOPS * 100, 2),
-            "gemm_phase": {"launches_per_call": cnt // reps, "ms_per_call": round(ms / reps, 4),
-                           "tflops": round(pf / ms * 1e-9, 2) if ms > 0 else None,
-                           "pct_of_peak": round(pf / ms * 1e-9 / PEAK_F64_MFMA_TFLOPS * 100, 2) if ms > 0 else None},
-            "diag_ms_per_call": round(dms / reps, 4), "trsm_ms_per_call": round(tms / reps, 4),
+            "tiled_gemm": gemm, "bulk_update": upd, "diag": diag, "solves_and_head": solve,
         }
-        gemm_ms += ms
-        gemm_fl += pf
-        gemm_launches += cnt
-    achieved = gemm_fl / gemm_ms * 1e-9 if gemm_ms > 0 else 0.0  # TFLOP/s
+        upd_ms += ums
+        upd_fl += ufl
+        upd_launches += ucnt
+    achieved = upd_fl / upd_ms * 1e-9 if upd_ms > 0 else 0.0  # TFLOP/s
+    la, ba = update_algorithmic_bytes(n, p_lu.nb or 128, False)
+    lc, bc = update_algorithmic_bytes(n, p_ch.nb or 128, True)
+    alg_launches, alg_bytes = la + lc, ba + bc
 
     # ---- CPU oracle on the host cores: one pass of the same workload ----------------------------
     cpu = None
@@ -174,11 +210,13 @@ def main() -> int:
         "pct_of_fp64_mfma_peak": round(gflops * 1e-3 / PEAK_F64_MFMA_TFLOPS * 100, 2),
         "kernels": kernels,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_F64_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": None,
-                     "kernel": "gemm_kernel (trailing updates + 3mm products)",
-                     "launches": gemm_launches, "avg_launch_ms": round(gemm_ms / max(gemm_launches, 1), 5),
-                     "flops_per_launch": round(gemm_fl / max(gemm_launches, 1), 1),
-                     "how": "per-launch HIP events on the kernel's stream, in a repeat of the timed steps"},
+                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "update_kernel (bulk trailing update of lu_factor and cholesky_factor, all launches)",
+                     "launches": upd_launches, "avg_launch_ms": round(upd_ms / max(upd_launches, 1), 5),
+                     "flops_per_launch": round(upd_fl / max(upd_launches, 1), 1),
+                     "algorithmic_bytes_per_launch": round(alg_bytes / max(alg_launches, 1), 1),
+                     "how": "per-launch HIP events on the stream the kernel runs on, in a repeat of the timed steps "
+                            "with the other streams of the pipeline running beside it"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -14,10 +14,12 @@
  *     *_workspace_bytes() query returns.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued on it asynchronously; no entry point synchronises
- *     the device.  With lookahead enabled a factorisation also uses one
- *     library-owned helper stream that is fork/joined to hip_stream with
+ *     the device.  With lookahead enabled a factorisation also uses two
+ *     library-owned helper streams that are fork/joined to hip_stream with
  *     events, so from the caller's side the call still behaves as one piece of
- *     work on hip_stream.
+ *     work on hip_stream.  The helper streams and their events are shared by
+ *     all calls of the process, so the entry points are not thread safe: calls
+ *     from several host threads must be serialised by the caller.
  *   - Return value: DLA_SUCCESS (0); -i when the i-th argument (1-based) is
  *     invalid (null pointer, negative size, leading dimension too small,
  *     unknown dtype, misaligned pointer); or one of the positive DLA_ERR_*
@@ -69,12 +71,15 @@ typedef struct {
 /*
  * Schedule of a blocked right-looking factorisation.  nb is the panel width
  * (block size), update the schedule of the trailing-matrix (Schur complement)
- * GEMM that dominates the run time.
+ * update that dominates the run time: all fields 0 (the default) selects the
+ * library's panel-stationary rank-nb update kernel, anything else runs the
+ * update as tiled GEMMs with that schedule, so that a search can drive it.
  */
 typedef struct {
   int nb;        /* block size, multiple of 16, 16..128 (0 = default)                          */
-  int lookahead; /* 0: one stream, strictly sequential steps; 1: factor panel k+1 on a helper
-                    stream while the rest of update k runs; -1 = default                       */
+  int lookahead; /* 0: one stream, strictly sequential steps; 1: the next diagonal block is factored
+                    while panel solves and trailing update of this step run on helper streams;
+                    -1 = default                                                               */
   dla_gemm_params update;
 } dla_factor_params;
 
@@ -167,7 +172,8 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out);
  * and mm3 bracket every launch of the named phase with events on the stream
  * the kernel runs on.  dla_profile_read synchronises those events and returns
  * accumulated milliseconds and launch counts, then clears them.
- * Phases: 0 = GEMM (trailing update / 3mm products), 1 = diagonal block, 2 = TRSM.
+ * Phases: 0 = tiled GEMM (3mm products, strip updates, caller-tiled trailing updates),
+ * 1 = diagonal block, 2 = panel solves and head update, 3 = bulk trailing update (default schedule).
  * Profiling is per process, not thread safe, and perturbs the pipeline; leave
  * it off when timing whole calls.
  */

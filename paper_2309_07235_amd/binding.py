@@ -21,7 +21,7 @@ DLA_F64, DLA_F32 = 0, 1
 DLA_SUCCESS, DLA_ERR_UNSUPPORTED_PARAMS, DLA_ERR_WORKSPACE, DLA_ERR_HIP, DLA_ERR_TOO_LARGE = 0, 1, 2, 3, 4
 DLA_KERNEL_MM3, DLA_KERNEL_LU, DLA_KERNEL_CHOLESKY = 0, 1, 2
 OP_ASSIGN, OP_SUB, OP_SUB_NT_LOWER = 0, 1, 2
-PHASE_GEMM, PHASE_DIAG, PHASE_TRSM = 0, 1, 2
+PHASE_GEMM, PHASE_DIAG, PHASE_TRSM, PHASE_UPDATE = 0, 1, 2, 3
 
 
 class GemmParams(ctypes.Structure):

@@ -99,7 +99,7 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
   }
   a.items = items;
   const double flops = (LOWER ? 1.0 : 2.0) * ((double)m * (double)m - (double)skip * (double)skip) * (double)b;
-  ProfileScope scope(PHASE_GEMM, flops, st);
+  ProfileScope scope(PHASE_UPDATE, flops, st);
   launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }

@@ -8,7 +8,7 @@
 
 namespace dla {
 
-enum Phase { PHASE_GEMM = 0, PHASE_DIAG = 1, PHASE_TRSM = 2, PHASE_COUNT = 3 };
+enum Phase { PHASE_GEMM = 0, PHASE_DIAG = 1, PHASE_TRSM = 2, PHASE_UPDATE = 3, PHASE_COUNT = 4 };
 
 // Fills defaults into a user schedule and checks it against the menu.
 // op selects which LDS layout the fit check uses.
