@@ -189,7 +189,7 @@ static int mm3_impl(const T* A, int64_t lda, const T* B, int64_t ldb, const T* C
     const int t0 = problem_tiles(se, OP_ASSIGN, g.prob[0]);
     g.prob[1] = make_problem<T>(se, OP_ASSIGN, C, ldc, D, ldd, F, L.ldf, nj, nl, nm, t0);
     g.total_tiles = t0 + problem_tiles(se, OP_ASSIGN, g.prob[1]);
-    g.prob[2] = g.prob[1];
+    for (int q = 2; q < kMaxGroup; ++q) g.prob[q] = g.prob[1];
     ProfileScope scope(PHASE_GEMM, 2.0 * ((double)ni * nj * nk + (double)nj * nl * nm), st);
     if ((rc = launch_gemm<T>(se, OP_ASSIGN, g, st)) != DLA_SUCCESS) return rc;
   } else {

@@ -13,15 +13,17 @@ constexpr int kChainCu = 32;  // left to the latency chain while a bulk update r
 
 static inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workspace: two parity sets of {inverted lower sub-blocks, inverted upper sub-blocks}.
+// Workspace: two parity sets of {inverted lower sub-blocks, inverted upper sub-blocks}, then two
+// parity sets of {copy of the row-panel head, copy of the column-panel head} (kNbMax x kNbMax each).
 static size_t inv_set_bytes(dla_dtype dt) {
   return round_up_sz((size_t)(kNbMax / kIb) * 256 * (dt == DLA_F64 ? 8 : 4), 256);
 }
+static size_t head_copy_bytes(dla_dtype dt) { return (size_t)kNbMax * kNbMax * (dt == DLA_F64 ? 8 : 4); }
 
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p) {
   (void)n;
   (void)p;
-  return 4 * inv_set_bytes(dt);
+  return 4 * inv_set_bytes(dt) + 4 * head_copy_bytes(dt);
 }
 
 int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
@@ -47,7 +49,7 @@ static inline void launch_ev(K kern, dim3 grid, dim3 block, int lds, hipStream_t
 }
 
 template <typename T, int KIND>
-static int launch_diag(const DiagArgs<T>& a, hipStream_t st) {
+static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = nullptr) {
   auto kern = diag_kernel<T, KIND>;
   static bool attr_done = false;
   if (!attr_done) {
@@ -57,7 +59,7 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st) {
     attr_done = true;
   }
   ProfileScope scope(PHASE_DIAG, 0.0, st);
-  hipLaunchKernelGGL(kern, dim3(1), dim3(kDiagThreads), diag_lds_bytes<T>(), st, a);
+  launch_ev(kern, dim3(1), dim3(kDiagThreads), diag_lds_bytes<T>(), st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
@@ -105,22 +107,23 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
 }
 
 template <typename T, int KIND>
-static int launch_trsm(TrsmArgs<T> a, hipStream_t st, hipEvent_t done = nullptr) {
-  auto kern = trsm_kernel<T, KIND>;
+static int launch_solve(SolveArgs<T> sa, hipStream_t st, hipEvent_t done = nullptr) {
+  if (sa.b % kIb != 0) return DLA_ERR_UNSUPPORTED_PARAMS;  // a panel with something behind it is always nb wide
+  auto kern = solve_kernel<T, KIND>;
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            trsm_lds_bytes<T>()) != hipSuccess)
+                            solve_lds_bytes<T>()) != hipSuccess)
       return DLA_ERR_HIP;
     attr_done = true;
   }
-  const int per_wg = (kTrsmThreads / 64) * kIb;  // panel rows/columns one workgroup solves
-  const int wgs = (a.m + per_wg - 1) / per_wg;
-  a.n_left = (KIND == KIND_LU) ? wgs : 0;
-  const int grid = a.n_left + wgs;
+  const int per_wg = (kSolveThreads / 64) * kIb;  // panel rows/columns one workgroup solves
+  const int wgs = (sa.m + per_wg - 1) / per_wg;
+  sa.n_top = (KIND == KIND_LU) ? wgs : 0;
+  const int grid = sa.n_top + wgs;
   if (grid <= 0) return DLA_SUCCESS;
   ProfileScope scope(PHASE_TRSM, 0.0, st);
-  launch_ev(kern, dim3((unsigned)grid), dim3(kTrsmThreads), trsm_lds_bytes<T>(), st, done, a);
+  launch_ev(kern, dim3((unsigned)grid), dim3(kSolveThreads), solve_lds_bytes<T>(), st, done, sa);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
@@ -147,7 +150,7 @@ static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done = n
 struct LookaheadCtx {
   hipStream_t panel = nullptr;  // panel solves + strip updates
   hipStream_t bulk = nullptr;   // bulk trailing updates
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   bool ok = false;
 };
 static LookaheadCtx& lookahead_ctx() {
@@ -155,7 +158,7 @@ static LookaheadCtx& lookahead_ctx() {
   if (!ctx.ok) {
     bool good = hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
-    for (int i = 0; i < 4 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 6 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
     ctx.ok = good;
   }
   return ctx;
@@ -189,7 +192,12 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   auto inv_lo_of = [&](int step) { return reinterpret_cast<T*>(wsb + (size_t)(2 * (step & 1)) * set); };
   auto inv_up_of = [&](int step) { return reinterpret_cast<T*>(wsb + (size_t)(2 * (step & 1) + 1) * set); };
 
-  auto diag = [&](int64_t k0, int step, hipStream_t s) -> int {
+  auto head_top_of = [&](int step) { return reinterpret_cast<T*>(wsb + 4 * set + (size_t)(2 * (step & 1)) * head_copy_bytes(dt)); };
+  auto head_side_of = [&](int step) {
+    return reinterpret_cast<T*>(wsb + 4 * set + (size_t)(2 * (step & 1) + 1) * head_copy_bytes(dt));
+  };
+
+  auto diag = [&](int64_t k0, int step, hipStream_t s, hipEvent_t done) -> int {
     DiagArgs<T> da;
     da.A = A + k0 * lda + k0;
     da.lda = lda;
@@ -198,7 +206,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     da.info = d_info;
     da.inv_lo = inv_lo_of(step);
     da.inv_up = inv_up_of(step);
-    return launch_diag<T, KIND>(da, s);
+    return launch_diag<T, KIND>(da, s, done);
   };
   // panel solves of the block column / block row behind diagonal block k0
   auto solves = [&](int64_t k0, int step, hipStream_t s, hipEvent_t done) -> int {
@@ -206,17 +214,17 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     const int64_t m = n - k0 - b;
     if (m == 0) return DLA_SUCCESS;
     T* const Akk = A + k0 * lda + k0;
-    TrsmArgs<T> ta;
-    ta.D = Akk;
-    ta.left = Akk + b;                  // A12: b x m
-    ta.right = Akk + (int64_t)b * lda;  // A21: m x b
-    ta.lda = lda;
-    ta.b = b;
-    ta.m = (int)m;
-    ta.n_left = 0;
-    ta.inv_lo = inv_lo_of(step);
-    ta.inv_up = inv_up_of(step);
-    return launch_trsm<T, KIND>(ta, s, done);
+    SolveArgs<T> sa;
+    sa.D = Akk;
+    sa.top = Akk + b;                  // A12: b x m
+    sa.side = Akk + (int64_t)b * lda;  // A21: m x b
+    sa.lda = lda;
+    sa.b = b;
+    sa.m = (int)m;
+    sa.n_top = 0;
+    sa.inv_lo = inv_lo_of(step);
+    sa.inv_up = inv_up_of(step);
+    return launch_solve<T, KIND>(sa, s, done);
   };
   // trailing-update schedule for an m x m update when the caller names the tile
   auto update_schedule = [&](int64_t) { return upd; };
@@ -264,7 +272,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
       const int b = (int)((n - k0 < nb) ? n - k0 : nb);
       const int64_t m = n - k0 - b;
-      if ((rc = diag(k0, step, st)) != DLA_SUCCESS) return rc;
+      if ((rc = diag(k0, step, st, nullptr)) != DLA_SUCCESS) return rc;
       if (m == 0) break;
       if ((rc = solves(k0, step, st, nullptr)) != DLA_SUCCESS) return rc;
       T* const Akk = A + k0 * lda + k0;
@@ -279,16 +287,19 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     //                     (what head(k+1) reads)
     //   bulk stream       bulk(k): step k's update of everything behind block row/column N except
     //                     block (N2,N2)
-    // Dependencies beyond stream order: head(k) after strips(k-1); solves(k) after head(k) (it
-    // overwrites the panel heads head(k) reads); strips(k) after bulk(k-1) (same memory);
-    // bulk(k) after solves(k).
+    // Dependencies beyond stream order: head(k) after strips(k-1); solves(k) after diag(k);
+    // strips(k) after bulk(k-1) (same memory); bulk(k) after solves(k).
+    // solves(k) overwrites the panel heads A[k][N], A[N][k] that head(k) reads, so strips(k-1), which
+    // produces those two blocks, also writes a copy of them to the workspace and head(k) reads the
+    // copies; only the first step reads them in place and makes solves(0) wait for head(0).
     LookaheadCtx& ctx = lookahead_ctx();
     if (!ctx.ok) return DLA_ERR_HIP;
     hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_strip = ctx.ev[2], e_bulk = ctx.ev[3];
+    hipEvent_t e_diag[2] = {ctx.ev[4], ctx.ev[5]};  // by step parity
     bool strip_pending = false, bulk_pending = false;
     constexpr int SOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT;
 
-    if ((rc = diag(0, 0, st)) != DLA_SUCCESS) return rc;
+    if ((rc = diag(0, 0, st, nullptr)) != DLA_SUCCESS) return rc;
     int step = 0;
     for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
       const int b = (int)((n - k0 < nb) ? n - k0 : nb);
@@ -306,19 +317,20 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       if (strip_pending && hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
       HeadArgs<T> ha;
       ha.D = Akk;
-      ha.top = U12;
-      ha.side = L21;
+      ha.top = step == 0 ? U12 : head_top_of(step);
+      ha.side = step == 0 ? L21 : head_side_of(step);
       ha.C = A22;
       ha.lda = lda;
+      ha.ldh = step == 0 ? lda : kNbMax;
       ha.b = b;
       ha.bn = (int)bn;
       ha.inv_lo = inv_lo_of(step);
       ha.inv_up = inv_up_of(step);
-      if ((rc = launch_head<T, KIND>(ha, st, e_head)) != DLA_SUCCESS) return rc;
-      if ((rc = diag(k0 + b, step + 1, st)) != DLA_SUCCESS) return rc;
+      if ((rc = launch_head<T, KIND>(ha, st, step == 0 ? e_head : nullptr)) != DLA_SUCCESS) return rc;
+      if ((rc = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return rc;
 
       // ---- panel stream: solves(k), strips(k)
-      if (hipStreamWaitEvent(ctx.panel, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
+      if (hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
       // the last kernel of the step on this stream carries e_strip
       if ((rc = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return rc;
       if (mr > 0) {
@@ -328,19 +340,28 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         GemmGroup<T> g;
         int np = 0, tiles = 0;
         double flops = 0.0;
-        auto add = [&](const T* a, const T* bm, T* c, int64_t M, int64_t N) {
+        auto add = [&](const T* a, const T* bm, T* c, int64_t M, int64_t N, T* copy) {
+          if (M <= 0 || N <= 0) return;
           g.prob[np] = make_problem<T>(ps, SOP, a, lda, bm, lda, c, lda, M, N, b, tiles);
+          g.prob[np].C2 = copy;
+          g.prob[np].ldc2 = kNbMax;
           tiles += problem_tiles(ps, SOP, g.prob[np]);
           flops += 2.0 * (double)M * (double)N * (double)b;
           ++np;
         };
+        const int64_t rest = mr - bn2;  // rows / columns behind block N2
+        T* const side_copy = head_side_of(step + 1);  // A[N2][N], the next step's column-panel head
+        T* const top_copy = head_top_of(step + 1);    // A[N][N2], the next step's row-panel head
         if (KIND == KIND_LU) {
-          add(Lr, U12, A22 + bn * lda, mr, bn);                   // block column N below block (N,N)
-          add(L21, U12 + bn, A22 + bn, bn, mr);                   // block row N right of block (N,N)
-          add(Lr, U12 + bn, A22 + bn * lda + bn, bn2, bn2);       // block (N2,N2)
+          add(Lr, U12, A22 + bn * lda, bn2, bn, side_copy);                              // block (N2,N)
+          add(Lr + bn2 * lda, U12, A22 + (bn + bn2) * lda, rest, bn, nullptr);           // block column N below it
+          add(L21, U12 + bn, A22 + bn, bn, bn2, top_copy);                               // block (N,N2)
+          add(L21, U12 + bn + bn2, A22 + bn + bn2, bn, rest, nullptr);                   // block row N right of it
+          add(Lr, U12 + bn, A22 + bn * lda + bn, bn2, bn2, nullptr);                     // block (N2,N2)
         } else {
-          add(Lr, L21, A22 + bn * lda, mr, bn);                   // block column N below block (N,N)
-          add(Lr, Lr, A22 + bn * lda + bn, bn2, bn2);             // block (N2,N2)
+          add(Lr, L21, A22 + bn * lda, bn2, bn, side_copy);                              // block (N2,N)
+          add(Lr + bn2 * lda, L21, A22 + (bn + bn2) * lda, rest, bn, nullptr);           // block column N below it
+          add(Lr, Lr, A22 + bn * lda + bn, bn2, bn2, nullptr);                           // block (N2,N2)
         }
         for (int q = np; q < kMaxGroup; ++q) g.prob[q] = g.prob[0];
         g.nprob = np;

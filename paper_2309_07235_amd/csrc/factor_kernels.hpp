@@ -8,11 +8,8 @@
 //                 triangular solves for the 16-wide inner panels, MFMA for the
 //                 inner trailing update.  It also inverts every 16 x 16
 //                 diagonal sub-block; the inverses go to the workspace.
-//   trsm_kernel   the large panel solves U12 = L11^-1 A12, L21 = A21 U11^-1 and
-//                 L21 = A21 L11^-T as blocked substitution on MFMA: each
-//                 wavefront owns a 16-wide slice of the panel in accumulator
-//                 registers, multiplies by the inverted diagonal sub-blocks and
-//                 eliminates with the off-diagonal sub-blocks staged in LDS.
+// The panel solves and the look-ahead head update, which consume those inverses,
+// live in head_kernel.hpp.
 #pragma once
 #include <type_traits>
 #include "dla_common.hpp"
@@ -28,7 +25,6 @@ constexpr int kNbMax = 128;            // largest block size
 constexpr int kIb = 16;                // inner block = one MFMA block
 constexpr int kSld = kNbMax + 1;       // odd LDS row stride of the diagonal block
 constexpr int kDiagThreads = 512;
-constexpr int kTrsmThreads = 256;
 constexpr int kBlk = kIb * (kIb + 1);  // 16 x 17: one padded 16 x 16 sub-block in LDS
 
 enum FactorKind { KIND_LU = 0, KIND_CHOL = 1 };
@@ -494,197 +490,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
 template <typename T>
 constexpr int diag_lds_bytes() {
   return ((kNbMax + 1) * kSld + kNbMax) * (int)sizeof(T);
-}
-
-// --------------------------------------------------------------------------------------
-// Panel solves.  JOB_LEFT:  X = L11^-1 * P,  P = b x m  (LU row panel, 16 columns per wave)
-//                JOB_RIGHT: X = P * R^-1,   P = m x b  (16 rows per wave), R = U11 (LU) or L11^T (Cholesky)
-template <typename T>
-struct TrsmArgs {
-  const T* D;       // factored diagonal block (top-left element), leading dimension lda
-  T* left;          // row panel  (b x m), may be null when n_left == 0
-  T* right;         // column panel (m x b)
-  int64_t lda;
-  int b, m;
-  int n_left;       // workgroups [0, n_left) do the row panel, the rest the column panel
-  const T* inv_lo;  // inverted diagonal sub-blocks of the lower factor
-  const T* inv_up;  // inverted diagonal sub-blocks of the upper factor (LU)
-};
-
-__device__ inline int tri_index(int hi, int lo) { return hi * (hi + 1) / 2 + lo; }
-
-template <typename T>
-constexpr int trsm_lds_bytes() {
-  constexpr int nb = kNbMax / kIb;
-  return (nb * (nb + 1) / 2 * kBlk + (kTrsmThreads / 64) * kBlk) * (int)sizeof(T);
-}
-
-template <typename T, int KIND>
-__global__ void __launch_bounds__(kTrsmThreads) trsm_kernel(const TrsmArgs<T> g) {
-  constexpr int NB = kNbMax / kIb;  // 8
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  T* const Tri = reinterpret_cast<T*>(smem_raw);         // compact lower-triangular set of padded sub-blocks
-  T* const scratch_all = Tri + NB * (NB + 1) / 2 * kBlk;  // one padded sub-block per wave
-  using acc_t = typename Mfma<T>::acc_t;
-
-  const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l15 = lane & 15, l4 = lane >> 4;
-  const int b = g.b, m = g.m;
-  const int nblk = (b + kIb - 1) / kIb;
-  const bool left = (int)blockIdx.x < g.n_left;
-  T* const scratch = scratch_all + wave * kBlk;
-
-  // ---- stage the triangular factor: off-diagonal sub-blocks negated, diagonal ones inverted ----
-  // LEFT needs L (strict lower blocks).  RIGHT/LU needs U (strict upper blocks, stored at
-  // tri_index(col block, row block)).  RIGHT/Cholesky needs L again.  One element per thread and
-  // sub-block; every load is issued before the first LDS store.
-  const bool want_upper = (!left) && KIND == KIND_LU;
-  DLA_TRACE(0);
-  {
-    const int rr = tid >> 4, cc = tid & 15;
-    T v[NB * (NB + 1) / 2];
-#pragma unroll
-    for (int hi = 0; hi < NB; ++hi)
-#pragma unroll
-      for (int lo = 0; lo <= hi; ++lo) {
-        const int t = hi * (hi + 1) / 2 + lo;
-        // unconditional loads from clamped addresses; masked afterwards
-        const int hc = hi < nblk ? hi : nblk - 1, lc = lo < nblk ? lo : nblk - 1;
-        if (hi == lo) {
-          v[t] = (want_upper ? g.inv_up : g.inv_lo)[hc * 256 + rr * 16 + cc];
-        } else {
-          const int gr = (want_upper ? lc : hc) * kIb + rr, gc = (want_upper ? hc : lc) * kIb + cc;
-          const T x = g.D[(int64_t)(gr < b ? gr : b - 1) * g.lda + (gc < b ? gc : b - 1)];
-          v[t] = (gr < b && gc < b) ? -x : T(0);
-        }
-      }
-#pragma unroll
-    for (int hi = 0; hi < NB; ++hi)
-#pragma unroll
-      for (int lo = 0; lo <= hi; ++lo)
-        if (hi < nblk) Tri[(hi * (hi + 1) / 2 + lo) * kBlk + rr * (kIb + 1) + cc] = v[hi * (hi + 1) / 2 + lo];
-  }
-  __syncthreads();
-  DLA_TRACE(1);
-
-  const int slice = ((left ? (int)blockIdx.x : (int)blockIdx.x - g.n_left) * (kTrsmThreads / 64) + wave) * kIb;
-  if (slice >= m) return;
-
-  acc_t acc[NB];
-  if (left) {
-    // ---------------- X = L11^-1 P : wave owns columns slice .. slice+15 ----------------
-    T* const P = g.left + slice;
-    const bool col_ok = slice + l15 < m;
-    const int colc = col_ok ? l15 : m - 1 - slice;  // clamped: loads are unconditional, masked afterwards
-#pragma unroll
-    for (int s = 0; s < NB; ++s)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = s * kIb + Mfma<T>::row_of(v, lane);
-        const T x = P[(int64_t)(row < b ? row : b - 1) * g.lda + colc];
-        acc[s][v] = (row < b && col_ok) ? x : T(0);
-      }
-    DLA_TRACE(2);
-#pragma unroll
-    for (int r = 0; r < NB; ++r) {
-      if (r < nblk) {
-        // right-hand operand fragments of X_r: rows 4*kk + l4, column l15
-        T fb[4];
-        auto to_b = [&](const acc_t& x) {
-          if constexpr (std::is_same<T, double>::value) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) fb[kk] = x[kk];  // fp64 result layout == B layout of k-step kk
-          } else {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-#pragma unroll
-            for (int v = 0; v < 4; ++v) scratch[Mfma<T>::row_of(v, lane) * (kIb + 1) + l15] = x[v];
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) fb[kk] = scratch[(kk * 4 + l4) * (kIb + 1) + l15];
-          }
-        };
-        to_b(acc[r]);
-        acc_t xr = {0, 0, 0, 0};
-        const T* dblk = Tri + tri_index(r, r) * kBlk + l15 * (kIb + 1) + l4;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) xr = Mfma<T>::mma(dblk[kk * 4], fb[kk], xr);
-        acc[r] = xr;
-        to_b(xr);
-#pragma unroll
-        for (int s = r + 1; s < NB; ++s) {
-          if (s < nblk) {
-            const T* oblk = Tri + tri_index(s, r) * kBlk + l15 * (kIb + 1) + l4;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) acc[s] = Mfma<T>::mma(oblk[kk * 4], fb[kk], acc[s]);
-          }
-        }
-      }
-    }
-    DLA_TRACE(3);
-#pragma unroll
-    for (int s = 0; s < NB; ++s)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = s * kIb + Mfma<T>::row_of(v, lane);
-        if (s < nblk && row < b && col_ok) P[(int64_t)row * g.lda + l15] = acc[s][v];
-      }
-    DLA_TRACE(4);
-  } else {
-    // ---------------- X = P R^-1 : wave owns rows slice .. slice+15 ----------------
-    T* const P = g.right + (int64_t)slice * g.lda;
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = Mfma<T>::row_of(v, lane), col = c * kIb + l15;
-        const T x = P[(int64_t)(slice + row < m ? row : m - 1 - slice) * g.lda + (col < b ? col : b - 1)];
-        acc[c][v] = (slice + row < m && col < b) ? x : T(0);
-      }
-    DLA_TRACE(5);
-#pragma unroll
-    for (int c = 0; c < NB; ++c) {
-      if (c < nblk) {
-        // left-hand operand fragments of a result block: rows l15, columns 4*kk + l4 (through LDS)
-        T fa[4];
-        auto to_a = [&](const acc_t& x) {
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-#pragma unroll
-          for (int v = 0; v < 4; ++v) scratch[Mfma<T>::row_of(v, lane) * (kIb + 1) + l15] = x[v];
-          __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) fa[kk] = scratch[l15 * (kIb + 1) + kk * 4 + l4];
-        };
-        // right-hand operand fragment of sub-block (row block s, column block d) of R, k-step kk
-        auto rfrag = [&](int s, int d, int kk) -> T {
-          const T* blk = Tri + tri_index(d, s) * kBlk;
-          if (KIND == KIND_LU) return blk[(kk * 4 + l4) * (kIb + 1) + l15];  // U stored as is
-          return blk[l15 * (kIb + 1) + kk * 4 + l4];                         // L stored; R = L^T
-        };
-        to_a(acc[c]);
-        acc_t xc = {0, 0, 0, 0};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) xc = Mfma<T>::mma(fa[kk], rfrag(c, c, kk), xc);
-        acc[c] = xc;
-        to_a(xc);
-#pragma unroll
-        for (int d = c + 1; d < NB; ++d) {
-          if (d < nblk) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) acc[d] = Mfma<T>::mma(fa[kk], rfrag(c, d, kk), acc[d]);
-          }
-        }
-      }
-    }
-    DLA_TRACE(6);
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = Mfma<T>::row_of(v, lane), col = c * kIb + l15;
-        if (c < nblk && slice + row < m && col < b) P[(int64_t)row * g.lda + col] = acc[c][v];
-      }
-    DLA_TRACE(7);
-  }
 }
 
 // Zero the strict upper triangle (Cholesky output convention).

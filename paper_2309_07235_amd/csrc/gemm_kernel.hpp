@@ -30,9 +30,11 @@ struct GemmProblem {
   int M, N, K;
   int tiles_m, tiles_n;
   int tile_begin;  // first logical tile id of this problem inside the group
+  T* C2;           // optional second destination of the result (same shape, leading dimension ldc2), or null
+  int64_t ldc2;
 };
 
-constexpr int kMaxGroup = 3;  // products one launch can carry
+constexpr int kMaxGroup = 5;  // products one launch can carry
 
 template <typename T>
 struct GemmGroup {
@@ -348,6 +350,18 @@ gemm_kernel(const GemmGroup<T> g) {
         const int r = a * 16 + Mfma<T>::row_of(v, lane), c = b * 16 + l15;
         if (full_mn || (m0 + wm0 + r < M && n0 + wn0 + c < N)) Cw[(int64_t)r * ldc + c] = acc[a][b][v];
       }
+  if (P.C2) {  // uniform: a copy of the result for a consumer that must not see later in-place changes
+    T* const Cw2 = P.C2 + (int64_t)(m0 + wm0) * P.ldc2 + (n0 + wn0);
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+      for (int b = 0; b < FN; ++b)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r = a * 16 + Mfma<T>::row_of(v, lane), c = b * 16 + l15;
+          if (full_mn || (m0 + wm0 + r < M && n0 + wn0 + c < N)) Cw2[(int64_t)r * P.ldc2 + c] = acc[a][b][v];
+        }
+  }
 }
 
 }  // namespace dla

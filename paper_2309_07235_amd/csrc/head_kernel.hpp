@@ -5,7 +5,8 @@
 // This kernel computes exactly that b x b piece (paper, Section "Linear Algebra Benchmarks": the
 // Schur-complement step of the two factorisations) straight from the un-solved panel heads, so the
 // next diagonal block can be factored while the full panel solves and the rest of the update run
-// on other streams.  The panel heads themselves are left untouched (the panel solve writes them).
+// on other streams.  The panel heads are only read, and may be given as copies, so the panel solve
+// that overwrites them in the matrix need not wait for this kernel.
 //
 // One workgroup of four wavefronts per 32 x 32 tile of the block.  The triangular factors (off-
 // diagonal 16 x 16 sub-blocks as they are, diagonal ones inverted) are staged in LDS with ONE round
@@ -38,7 +39,8 @@ struct HeadArgs {
   const T* top;     // LU: block (k, k+1), b x bn.  Cholesky: unused
   const T* side;    // block (k+1, k), bn x b
   T* C;             // block (k+1, k+1), bn x bn
-  int64_t lda;      // common leading dimension
+  int64_t lda;      // leading dimension of D and C
+  int64_t ldh;      // leading dimension of top and side (they may be copies outside the matrix)
   int b, bn;        // b: multiple of 16, <= kNbMax;  1 <= bn <= kNbMax
   const T* inv_lo;  // inverted diagonal sub-blocks of the lower factor
   const T* inv_up;  // inverted diagonal sub-blocks of the upper factor (LU)
@@ -57,7 +59,7 @@ __device__ inline int head_prow(int l15) {
   else return l15;
 }
 
-// X = M^-1 * P for a lower-triangular M whose sub-block (s, r), s >= r, sits at tri[tri_index(s, r)]
+// X = M^-1 * P for a lower-triangular M whose sub-block (s, r), s >= r, sits at tri[s * (s + 1) / 2 + r]
 // (diagonal ones inverted); element (i, k) of a sub-block at i * rs + k * cs.  acc holds P on entry
 // and X on return: register v of acc[s] is row 16 * s + 4 * (lane / 16) + v, column lane % 16.
 template <typename T, bool FULL>
@@ -97,7 +99,7 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
   using acc_t = typename Mfma<T>::acc_t;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   T* const triL = reinterpret_cast<T*>(smem_raw);  // lower factor
-  T* const triU = triL + NTRI * kBlk;              // upper factor (LU): sub-block (lo, hi) of U at tri_index(hi, lo)
+  T* const triU = triL + NTRI * kBlk;              // upper factor (LU): sub-block (lo, hi) of U at slot hi * (hi + 1) / 2 + lo
   T* const slices = triL;                          // after the solves: 4 slices of NB * 4 * 64 values
 
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -147,8 +149,8 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
     const int t_valid = bn - slice0 < kIb ? bn - slice0 : kIb;
     const int t = slice0 + (l15 < t_valid ? l15 : t_valid - 1);
     // element (k, t) of the right-hand side: top[k][t] for the X job, side[t][k] otherwise
-    const T* const prhs = x_job ? g.top + (int64_t)(4 * l4) * lda + t : g.side + (int64_t)t * lda + 4 * l4;
-    const int64_t ks = x_job ? lda : 1;
+    const T* const prhs = x_job ? g.top + (int64_t)(4 * l4) * g.ldh + t : g.side + (int64_t)t * g.ldh + 4 * l4;
+    const int64_t ks = x_job ? g.ldh : 1;
 #pragma unroll
     for (int s = 0; s < NB; ++s) {
       if (job_on && s < nblk) {
@@ -223,6 +225,112 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
   for (int v = 0; v < 4; ++v) {
     const int r = Mfma<T>::row_of(v, lane);
     if (r < rows_valid && l15 < cols_valid) Ct[(int64_t)r * lda + l15] = c[v];
+  }
+}
+
+// --------------------------------------------------------------------------------------
+// Panel solves with the same machinery: U12 = L11^-1 * A12 (LU row panel, 16 columns per wave) and
+// L21 = A21 * R^-1 (column panel, 16 rows per wave; R = U11 for LU, L11^T for Cholesky), the latter
+// as the transposed system, so a lane reads and writes runs of four consecutive elements of its
+// row and no result block has to be transposed through LDS.
+constexpr int kSolveThreads = 256;
+
+template <typename T>
+struct SolveArgs {
+  const T* D;       // factored diagonal block (b x b), leading dimension lda
+  T* top;           // row panel  (b x m), LU only
+  T* side;          // column panel (m x b)
+  int64_t lda;
+  int b, m;         // b: multiple of 16, <= kNbMax
+  int n_top;        // workgroups [0, n_top) solve the row panel, the rest the column panel
+  const T* inv_lo;
+  const T* inv_up;
+};
+
+template <typename T>
+constexpr int solve_lds_bytes() {
+  constexpr int nb = kNbMax / kIb;
+  return (nb * (nb + 1) / 2) * kBlk * (int)sizeof(T);
+}
+
+template <typename T, int KIND>
+__global__ void __launch_bounds__(kSolveThreads) solve_kernel(const SolveArgs<T> g) {
+  constexpr int NB = kNbMax / kIb;
+  constexpr int HALF = NB * (NB + 1) / 4;  // 18 of the 36 sub-blocks per staging pass
+  using acc_t = typename Mfma<T>::acc_t;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  T* const tri = reinterpret_cast<T*>(smem_raw);
+
+  const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l15 = lane & 15, l4 = lane >> 4;
+  const int b = g.b, m = g.m, nblk = b / kIb;
+  const int64_t lda = g.lda;
+  const bool x_job = KIND == KIND_LU && (int)blockIdx.x < g.n_top;
+  const bool upper = KIND == KIND_LU && !x_job;  // the factor this workgroup needs: U (as U^T), else L
+  const int wg = x_job ? (int)blockIdx.x : (int)blockIdx.x - g.n_top;
+  const int slice0 = (wg * (kSolveThreads / 64) + wave) * kIb;
+  const bool job_on = slice0 < m;
+
+  // ---- right-hand side into the accumulators: element (k, t) is top[k][t] or side[t][k] ---------
+  const int t_valid = m - slice0 < kIb ? m - slice0 : kIb;
+  const int t = slice0 + (l15 < t_valid ? l15 : t_valid - 1);
+  T* const prhs = x_job ? g.top + (int64_t)(4 * l4) * lda + t : g.side + (int64_t)t * lda + 4 * l4;
+  const int64_t ks = x_job ? lda : 1;
+  acc_t acc[NB];
+#pragma unroll
+  for (int s = 0; s < NB; ++s) {
+    if (job_on && s < nblk) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[s][v] = prhs[(int64_t)(s * kIb + v) * ks];
+    } else {
+      acc[s] = acc_t{0, 0, 0, 0};
+    }
+  }
+
+  // ---- stage the factor (two passes keep the staging registers few) -----------------------------
+  {
+    const int rr = tid >> 4, cc = tid & 15;
+    const T* const inv = upper ? g.inv_up : g.inv_lo;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      T v[HALF];
+#pragma unroll
+      for (int q = 0; q < HALF; ++q) {
+        const int tb = pass * HALF + q;
+        // tb -> (hi, lo), compile-time after unrolling
+        int hi = 0;
+        while ((hi + 1) * (hi + 2) / 2 <= tb) ++hi;
+        const int lo = tb - hi * (hi + 1) / 2;
+        if (hi < nblk) {
+          if (hi == lo) v[q] = inv[hi * 256 + rr * 16 + cc];
+          else if (upper) v[q] = g.D[(int64_t)(lo * kIb + rr) * lda + hi * kIb + cc];
+          else v[q] = g.D[(int64_t)(hi * kIb + rr) * lda + lo * kIb + cc];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < HALF; ++q) {
+        const int tb = pass * HALF + q;
+        int hi = 0;
+        while ((hi + 1) * (hi + 2) / 2 <= tb) ++hi;
+        if (hi < nblk) tri[tb * kBlk + rr * (kIb + 1) + cc] = v[q];
+      }
+    }
+  }
+  __syncthreads();
+  if (!job_on) return;
+  {
+    const int rs = upper ? 1 : kIb + 1, cs = upper ? kIb + 1 : 1;
+    if (nblk == NB) head_solve<T, true>(tri, rs, cs, nblk, lane, acc);
+    else head_solve<T, false>(tri, rs, cs, nblk, lane, acc);
+  }
+  if (l15 < t_valid) {
+#pragma unroll
+    for (int s = 0; s < NB; ++s) {
+      if (s < nblk) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) prhs[(int64_t)(s * kIb + v) * ks] = acc[s][v];
+      }
+    }
   }
 }
 

@@ -32,6 +32,8 @@ inline GemmProblem<T> make_problem(const GemmSchedule& s, int op, const T* A, in
   p.tiles_m = (int)((M + s.tm - 1) / s.tm);
   p.tiles_n = (int)((N + s.tn - 1) / s.tn);
   p.tile_begin = tile_begin;
+  p.C2 = nullptr;
+  p.ldc2 = 0;
   return p;
 }
 
