@@ -27,7 +27,7 @@ METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
 # HBM bytes per launch of the bulk update kernel (fetch + write), from the two rocprofv3 --pmc passes
 # summarised in profiles/update_kernel_hbm_traffic_n4000.txt (counter readings scaled by the same
 # counters' readings for a device copy of known size).  None until measured.
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74550 * 1024
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74540 * 1024
 
 
 def update_algorithmic_bytes(n, nb=128, lower=False):

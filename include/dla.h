@@ -149,6 +149,19 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
              int64_t ldc, int64_t m, int64_t n, int64_t k, dla_dtype dt, const dla_gemm_params* p,
              void* hip_stream);
 
+/*
+ * The default trailing update of the factorisations on its own (paper, Section "Linear Algebra
+ * Benchmarks": the Schur-complement step), exported so that it can be timed and tested in isolation:
+ *   lower == 0:  C -= L*R          L m x k, R k x m, C m x m            (LU)
+ *   lower == 1:  lower(C) -= L*L^T in blocks of 128 rows: row block i is updated in columns
+ *                0 .. 128*(i+1)-1, so the part of diagonal blocks above the diagonal changes too;
+ *                d_r is ignored                                          (Cholesky)
+ * k <= 128.  All three matrices share the leading dimension ld (they are parts of one matrix in the
+ * factorisations).  C must not overlap L or R.
+ */
+int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int64_t ld, int64_t m, int64_t k,
+                    dla_dtype dt, void* hip_stream);
+
 /* 1 if the schedule is in the menu for dt (fields equal to 0 are filled with defaults first), else 0. */
 int dla_gemm_params_supported(dla_dtype dt, const dla_gemm_params* p);
 

@@ -70,6 +70,8 @@ def _load() -> ctypes.CDLL:
     lib.mm3_workspace_bytes.restype = sz
     lib.dla_gemm.argtypes = [ci, vp, i64, vp, i64, vp, i64, i64, i64, i64, ci, ctypes.POINTER(GemmParams), vp]
     lib.dla_gemm.restype = ci
+    lib.dla_rank_update.argtypes = [ci, vp, vp, vp, i64, i64, i64, ci, vp]
+    lib.dla_rank_update.restype = ci
     lib.dla_gemm_params_supported.argtypes = [ci, ctypes.POINTER(GemmParams)]
     lib.dla_gemm_params_supported.restype = ci
     lib.dla_enumerate_tiles.argtypes = [ci, ctypes.POINTER(GemmParams), ci]
@@ -221,6 +223,19 @@ def dla_gemm(op: int, a, b, c, p: GemmParams | None = None, stream=None):
     (ap, lda), (bp, ldb), (cp, ldc) = _matrix(a, "a"), _matrix(b, "b"), _matrix(c, "c")
     _check(lib.dla_gemm(op, ap, lda, bp, ldb, cp, ldc, m, n, k, dt, _ref(p), ctypes.c_void_p(_stream_ptr(stream))),
            "dla_gemm")
+
+
+def dla_rank_update(lower: bool, l, r, c, stream=None):
+    """c -= l*r (lower False) or lower(c) -= l*l^T in 128-row blocks (lower True); see dla.h: dla_rank_update.
+    l, r and c must share one leading dimension (views into one matrix)."""
+    m, k = l.shape
+    dt = _dtype_code(l)
+    (lp, ldl), (cp, ldc) = _matrix(l, "l"), _matrix(c, "c")
+    rp, ldr = (None, ldl) if lower else _matrix(r, "r")
+    if not (ldl == ldc == ldr):
+        raise ValueError("dla_rank_update: l, r and c must share one leading dimension")
+    _check(lib.dla_rank_update(1 if lower else 0, lp, rp, cp, ldl, m, k, dt, ctypes.c_void_p(_stream_ptr(stream))),
+           "dla_rank_update")
 
 
 def profile_enable(on: bool) -> None:

@@ -303,6 +303,25 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   return run_gemm<float>(s, op, (const float*)d_a, lda, (const float*)d_b, ldb, (float*)d_c, ldc, m, n, k, st);
 }
 
+int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int64_t ld, int64_t m, int64_t k,
+                    dla_dtype dt, void* hip_stream) {
+  if (lower != 0 && lower != 1) return -1;
+  if (m < 0) return -6;
+  if (k < 0 || k > 128) return -7;
+  if (dt != DLA_F64 && dt != DLA_F32) return -8;
+  if (m > kMaxDim) return DLA_ERR_TOO_LARGE;
+  if (m == 0 || k == 0) return DLA_SUCCESS;
+  const size_t es = (size_t)esize(dt);
+  if (!d_l || (uintptr_t)d_l % es) return -2;
+  if (!lower && (!d_r || (uintptr_t)d_r % es)) return -3;
+  if (!d_c || (uintptr_t)d_c % es) return -4;
+  if (ld < m || ld < k) return -5;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return rank_update_impl<double>(lower != 0, (const double*)d_l, (const double*)d_r, (double*)d_c, ld, m, (int)k, st);
+  return rank_update_impl<float>(lower != 0, (const float*)d_l, (const float*)d_r, (float*)d_c, ld, m, (int)k, st);
+}
+
 size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt) {
   if (ni < 0 || nj < 0 || nl < 0 || (dt != DLA_F64 && dt != DLA_F32)) return 0;
   if (ni > kMaxDim || nj > kMaxDim || nl > kMaxDim) return 0;

@@ -395,6 +395,14 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
 }
 
 template <typename T>
+int rank_update_impl(bool lower, const T* L, const T* Rm, T* C, int64_t ld, int64_t m, int b, hipStream_t st) {
+  if (lower) return launch_update<T, KIND_CHOL>(L, L, C, ld, m, b, 0, kNumCu, st);
+  return launch_update<T, KIND_LU>(L, Rm, C, ld, m, b, 0, kNumCu, st);
+}
+template int rank_update_impl<double>(bool, const double*, const double*, double*, int64_t, int64_t, int, hipStream_t);
+template int rank_update_impl<float>(bool, const float*, const float*, float*, int64_t, int64_t, int, hipStream_t);
+
+template <typename T>
 int lu_factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
                    hipStream_t st, int* d_info) {
   return factor_impl<T, KIND_LU>(A, n, lda, p, ws, ws_bytes, st, d_info);

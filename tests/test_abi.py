@@ -136,5 +136,14 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.dla_gemm(0, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3
     assert L.dla_gemm(2, fake, 8, fake, 8, fake, 8, 8, 6, 8, B.DLA_F64, None, None) == -9
     assert L.dla_gemm(0, fake, 8, fake, 8, fake, 8, 0, 8, 8, B.DLA_F64, None, None) == 0
+    assert L.dla_rank_update(2, fake, fake, fake, 256, 64, 16, B.DLA_F64, None) == -1
+    assert L.dla_rank_update(0, None, fake, fake, 256, 64, 16, B.DLA_F64, None) == -2
+    assert L.dla_rank_update(0, fake, None, fake, 256, 64, 16, B.DLA_F64, None) == -3
+    assert L.dla_rank_update(1, fake, None, None, 256, 64, 16, B.DLA_F64, None) == -4
+    assert L.dla_rank_update(0, fake, fake, fake, 32, 64, 16, B.DLA_F64, None) == -5
+    assert L.dla_rank_update(0, fake, fake, fake, 256, -1, 16, B.DLA_F64, None) == -6
+    assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 129, B.DLA_F64, None) == -7
+    assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 16, 5, None) == -8
+    assert L.dla_rank_update(0, fake, fake, fake, 256, 0, 16, B.DLA_F64, None) == 0
     ms = ctypes.c_double()
     assert L.dla_profile_read(9, ctypes.byref(ms), None, None) == -1

@@ -308,3 +308,32 @@ def test_fp32_factorisations(B, oracle, n, nb):
     got, info = _gpu_chol(B, S32, _fparams(B, nb), dtype=torch.float32)
     assert info == 0
     _check_chol(oracle, got.astype(np.float64), S32.astype(np.float64), n, TOL32, EPS32)
+
+
+@pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96)])
+@pytest.mark.parametrize("lower", [False, True])
+def test_rank_update_alone(B, oracle, m, k, lower):
+    """dla_rank_update (the bulk trailing update on its own) against the oracle's plain product (the E of a
+    3mm whose second product is empty-sized): ragged row panels, ragged 32-column blocks, partial k."""
+    import torch
+    announce(f"rank_update m={m} k={k} lower={lower}")
+    n = m + k
+    A = inputs.uniform_matrix(11, 3, n, n)
+    a = to_device(A)
+    L, R, C = a[k:, :k], a[:k, k:], a[k:, k:]
+    B.dla_rank_update(lower, L, R, C)
+    torch.cuda.synchronize()
+    got = to_host(a)
+    exp = A.copy()
+    def product(X, Y):
+        return oracle.mm3(X, Y, np.zeros((Y.shape[1], 1)), np.zeros((1, 1)), return_intermediates=True)[1]
+
+    if lower:
+        full = A[k:, k:] - product(A[k:, :k], np.ascontiguousarray(A[k:, :k].T))
+        for r0 in range(0, m, 128):  # row block i is updated in columns 0 .. 128*(i+1)-1
+            r1, c1 = min(r0 + 128, m), min(r0 + 128, m)
+            exp[k + r0:k + r1, k:k + c1] = full[r0:r1, :c1]
+    else:
+        exp[k:, k:] = A[k:, k:] - product(A[k:, :k], A[:k, k:])
+    assert np.array_equal(got[:k, :], A[:k, :]) and np.array_equal(got[:, :k], A[:, :k]), "operands must stay untouched"
+    assert max_rel_err(got[k:, k:], exp[k:, k:]) <= TOL64
