@@ -337,3 +337,30 @@ def test_rank_update_alone(B, oracle, m, k, lower):
         exp[k:, k:] = A[k:, k:] - product(A[k:, :k], A[:k, k:])
     assert np.array_equal(got[:k, :], A[:k, :]) and np.array_equal(got[:, :k], A[:, :k]), "operands must stay untouched"
     assert max_rel_err(got[k:, k:], exp[k:, k:]) <= TOL64
+
+
+def test_back_to_back_calls_share_the_helper_streams(B, oracle):
+    """Five factorisations of different sizes and kinds enqueued on one side stream without any
+    synchronisation in between (the look-ahead helper streams and events are shared by all calls):
+    every result must still match the oracle."""
+    import torch
+    announce("back-to-back mixed calls, no sync in between")
+    cases = [("lu", 700, 128), ("chol", 517, 64), ("lu", 300, 48), ("chol", 1000, 128), ("lu", 129, 16)]
+    hosts, devs = [], []
+    for kind, n, nb in cases:
+        H = inputs.general_dominant_matrix(n, 60 + n) if kind == "lu" else inputs.spd_matrix(n, 60 + n)
+        hosts.append(H)
+        devs.append(to_device(H))
+    ws = torch.empty(B.factor_workspace_bytes(1000, B.DLA_F64, None), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for (kind, n, nb), d in zip(cases, devs):
+            fn = B.lu_factor if kind == "lu" else B.cholesky_factor
+            fn(d, _fparams(B, nb), workspace=ws)
+    s.synchronize()
+    for (kind, n, nb), H, d in zip(cases, hosts, devs):
+        if kind == "lu":
+            _check_lu(oracle, to_host(d), H, n)
+        else:
+            _check_chol(oracle, to_host(d), H, n)
