@@ -193,6 +193,16 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out);
 int dla_profile_enable(int on);
 int dla_profile_read(int phase, double* ms_total, int64_t* launches, double* flops);
 
+/*
+ * Achievable matrix-pipe peak: runs a register-resident 16x16x4 MFMA loop of the given type on the
+ * whole chip (about 2 ms, three times) and reports the fastest pass in TFLOP/s, the yardstick next
+ * to the published peak when a GEMM's efficiency is quoted.  Unlike every other entry point it
+ * synchronises hip_stream (it times itself with events).  d_scratch: device, 8-byte aligned, at
+ * least dla_mfma_peak_scratch_bytes() bytes, overwritten.
+ */
+int dla_mfma_peak(dla_dtype dt, void* d_scratch, size_t scratch_bytes, void* hip_stream, double* tflops);
+size_t dla_mfma_peak_scratch_bytes(void);
+
 const char* dla_strerror(int code);
 const char* dla_version(void);
 

@@ -70,6 +70,10 @@ def _load() -> ctypes.CDLL:
     lib.mm3_workspace_bytes.restype = sz
     lib.dla_gemm.argtypes = [ci, vp, i64, vp, i64, vp, i64, i64, i64, i64, ci, ctypes.POINTER(GemmParams), vp]
     lib.dla_gemm.restype = ci
+    lib.dla_mfma_peak.argtypes = [ci, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.dla_mfma_peak.restype = ci
+    lib.dla_mfma_peak_scratch_bytes.argtypes = []
+    lib.dla_mfma_peak_scratch_bytes.restype = ctypes.c_size_t
     lib.dla_rank_update.argtypes = [ci, vp, vp, vp, i64, i64, i64, ci, vp]
     lib.dla_rank_update.restype = ci
     lib.dla_gemm_params_supported.argtypes = [ci, ctypes.POINTER(GemmParams)]
@@ -236,6 +240,17 @@ def dla_rank_update(lower: bool, l, r, c, stream=None):
         raise ValueError("dla_rank_update: l, r and c must share one leading dimension")
     _check(lib.dla_rank_update(1 if lower else 0, lp, rp, cp, ldl, m, k, dt, ctypes.c_void_p(_stream_ptr(stream))),
            "dla_rank_update")
+
+
+def mfma_peak(dt: int = DLA_F64, stream=None) -> float:
+    """Achievable MFMA peak of the device in TFLOP/s for the given element type (see dla.h: dla_mfma_peak)."""
+    import torch
+    nbytes = int(lib.dla_mfma_peak_scratch_bytes())
+    scratch = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = ctypes.c_double()
+    _check(lib.dla_mfma_peak(dt, ctypes.c_void_p(scratch.data_ptr()), nbytes, ctypes.c_void_p(_stream_ptr(stream)),
+                             ctypes.byref(out)), "dla_mfma_peak")
+    return out.value
 
 
 def profile_enable(on: bool) -> None:

@@ -201,6 +201,53 @@ static int mm3_impl(const T* A, int64_t lda, const T* B, int64_t ldb, const T* C
 
 static const int64_t kMaxDim = (int64_t)1 << 30;
 
+// Register-resident MFMA loop: what the matrix pipes sustain when nothing else limits them.
+template <typename T>
+__global__ void __launch_bounds__(256) mfma_peak_kernel(T* out, int iters) {
+  using acc_t = typename Mfma<T>::acc_t;
+  constexpr int ILP = 4;
+  acc_t acc[ILP];
+#pragma unroll
+  for (int i = 0; i < ILP; ++i) acc[i] = acc_t{0, 0, 0, 0};
+  const T a = T(1e-3) * (T)threadIdx.x, b = T(1) + T(1e-4) * (T)threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < ILP; ++i) acc[i] = Mfma<T>::mma(a, b, acc[i]);
+  }
+  T s = 0;
+#pragma unroll
+  for (int i = 0; i < ILP; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+constexpr int kPeakGrid = 1024, kPeakIters = 4000;
+
+template <typename T>
+static int mfma_peak_impl(void* scratch, hipStream_t st, double* tflops) {
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return DLA_ERR_HIP;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    hipEventDestroy(e0);
+    return DLA_ERR_HIP;
+  }
+  float best = 0.0f;
+  bool ok = true;
+  for (int rep = 0; rep < 3 && ok; ++rep) {  // first pass warms the clocks up, the fastest of three counts
+    ok = hipEventRecord(e0, st) == hipSuccess;
+    hipLaunchKernelGGL(mfma_peak_kernel<T>, dim3(kPeakGrid), dim3(256), 0, st, static_cast<T*>(scratch), kPeakIters);
+    ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(e1, st) == hipSuccess &&
+         hipEventSynchronize(e1) == hipSuccess;
+    float ms = 0.0f;
+    ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    if (ok && ms > 0.0f && (best == 0.0f || ms < best)) best = ms;
+  }
+  hipEventDestroy(e0);
+  hipEventDestroy(e1);
+  if (!ok || best <= 0.0f) return DLA_ERR_HIP;
+  const double flops = (double)kPeakGrid * 4 /*waves*/ * kPeakIters * 4 /*ILP*/ * 2048.0;  // 16*16*4*2 per MFMA
+  *tflops = flops / (best * 1e-3) * 1e-12;
+  return DLA_SUCCESS;
+}
+
 }  // namespace dla
 
 using namespace dla;
@@ -320,6 +367,17 @@ int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int6
   if (dt == DLA_F64)
     return rank_update_impl<double>(lower != 0, (const double*)d_l, (const double*)d_r, (double*)d_c, ld, m, (int)k, st);
   return rank_update_impl<float>(lower != 0, (const float*)d_l, (const float*)d_r, (float*)d_c, ld, m, (int)k, st);
+}
+
+size_t dla_mfma_peak_scratch_bytes(void) { return (size_t)kPeakGrid * 256 * sizeof(double); }
+
+int dla_mfma_peak(dla_dtype dt, void* d_scratch, size_t scratch_bytes, void* hip_stream, double* tflops) {
+  if (dt != DLA_F64 && dt != DLA_F32) return -1;
+  if (!d_scratch || (uintptr_t)d_scratch % 8) return -2;
+  if (scratch_bytes < dla_mfma_peak_scratch_bytes()) return DLA_ERR_WORKSPACE;
+  if (!tflops) return -5;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  return dt == DLA_F64 ? mfma_peak_impl<double>(d_scratch, st, tflops) : mfma_peak_impl<float>(d_scratch, st, tflops);
 }
 
 size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt) {

@@ -145,5 +145,11 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 129, B.DLA_F64, None) == -7
     assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 16, 5, None) == -8
     assert L.dla_rank_update(0, fake, fake, fake, 256, 0, 16, B.DLA_F64, None) == 0
+    tf = ctypes.c_double()
+    assert L.dla_mfma_peak(7, fake, 1 << 22, None, ctypes.byref(tf)) == -1
+    assert L.dla_mfma_peak(B.DLA_F64, None, 1 << 22, None, ctypes.byref(tf)) == -2
+    assert L.dla_mfma_peak(B.DLA_F64, fake, 16, None, ctypes.byref(tf)) == B.DLA_ERR_WORKSPACE
+    assert L.dla_mfma_peak(B.DLA_F64, fake, 1 << 22, None, None) == -5
+    assert L.dla_mfma_peak_scratch_bytes() == 1024 * 256 * 8
     ms = ctypes.c_double()
     assert L.dla_profile_read(9, ctypes.byref(ms), None, None) == -1
