@@ -136,6 +136,14 @@ def test_cholesky_n1024_nb64(B, oracle):
     _check_chol(oracle, got, A, 1024)
 
 
+def test_cholesky_n2000_large_dataset(B, oracle):
+    announce("cholesky N=2000 (the paper's large dataset), default schedule")
+    A = inputs.spd_matrix(2000, 3)
+    got, info = _gpu_chol(B, A)
+    assert info == 0
+    _check_chol(oracle, got, A, 2000)
+
+
 def test_lu_n2000_nb128(B, oracle):
     announce("lu N=2000 nb=128 (last block 80)")
     A = inputs.diag_dominant_matrix(2000, 3)

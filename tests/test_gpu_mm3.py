@@ -103,6 +103,16 @@ def test_extralarge_config_full_size(B, oracle):
     assert np.array_equal(_run_mm3(B, iops), oracle.mm3(*iops))
 
 
+def test_large_dataset(B, oracle):
+    """The paper's "large" 3mm dataset: (N, L, M, O, P) = (800, 900, 1000, 1100, 1200)."""
+    announce("mm3 large dataset")
+    ops = inputs.mm3_operands(6, **inputs.MM3_LARGE_PAPER_ORDER)
+    want = oracle.mm3(*ops)
+    got = _run_mm3(B, ops)
+    assert max_rel_err(got, want) <= TOL64
+    assert fro_rel_err(got, want) <= 10 * 1100 * EPS64
+
+
 def test_paper_literal_dimension_order(B, oracle):
     """The paper's own assignment of the five extralarge sizes (N, L, M, O, P) = (1600, 1800, 2000, 2200, 2400)."""
     announce("mm3 paper-order extralarge")
