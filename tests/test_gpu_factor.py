@@ -318,6 +318,41 @@ def test_fp32_factorisations(B, oracle, n, nb):
     _check_chol(oracle, got.astype(np.float64), S32.astype(np.float64), n, TOL32, EPS32)
 
 
+def test_n8192_fp32_properties(B, oracle):
+    """The fp32 variant at N=8192, block size 128: exact all-ones factors of the min-index matrix (every
+    intermediate is an integer below 2^24), and randomised reconstruction checks of the seeded inputs rounded to
+    fp32, with the oracle's fp64 matrix-vector routines applied to the fp32 data."""
+    import torch
+    n = 8192
+    announce("fp32 N=8192 min-index exact")
+    A = inputs.min_index_matrix(n)
+    got, info = _gpu_lu(B, A, dtype=torch.float32)
+    assert info == 0 and got.dtype == np.float32 and np.array_equal(got, np.ones((n, n), dtype=np.float32))
+    got, info = _gpu_chol(B, A, dtype=torch.float32)
+    assert info == 0 and np.array_equal(got, np.tril(np.ones((n, n), dtype=np.float32)))
+    del A, got
+    announce("fp32 N=8192 LU reconstruction")
+    A32 = inputs.diag_dominant_matrix(n, 6).astype(np.float32)
+    lu, info = _gpu_lu(B, A32, dtype=torch.float32)
+    assert info == 0
+    A64, lu64 = A32.astype(np.float64), lu.astype(np.float64)
+    for t in range(3):
+        x = inputs.uniform_matrix(6, 70 + t, n, 1).ravel()
+        y0, y1 = oracle.matvec(A64, x), oracle.lu_apply(lu64, x)
+        assert np.linalg.norm(y0 - y1) <= 10 * n * EPS32 * np.linalg.norm(y0)
+    del lu, lu64
+    announce("fp32 N=8192 Cholesky reconstruction")
+    A64[np.diag_indices(n)] += 1.0 - float(n)  # the SPD generator: same Gram matrix, +I
+    S32 = A64.astype(np.float32)
+    L, info = _gpu_chol(B, S32, dtype=torch.float32)
+    assert info == 0 and np.all(np.triu(L, 1) == 0.0)
+    S64, L64 = S32.astype(np.float64), L.astype(np.float64)
+    for t in range(3):
+        x = inputs.uniform_matrix(6, 80 + t, n, 1).ravel()
+        y0, y1 = oracle.symv_lower(S64, x), oracle.cholesky_apply(L64, x)
+        assert np.linalg.norm(y0 - y1) <= 10 * n * EPS32 * np.linalg.norm(y0)
+
+
 @pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96)])
 @pytest.mark.parametrize("lower", [False, True])
 def test_rank_update_alone(B, oracle, m, k, lower):
