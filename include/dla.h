@@ -14,10 +14,13 @@
  *     *_workspace_bytes() query returns.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued on it asynchronously; no entry point synchronises
- *     the device.  With lookahead enabled a factorisation also uses two
+ *     the device.  With lookahead enabled a factorisation also uses three
  *     library-owned helper streams that are fork/joined to hip_stream with
  *     events, so from the caller's side the call still behaves as one piece of
- *     work on hip_stream.  The helper streams and their events are shared by
+ *     work on hip_stream.  Some of its kernels are then launched before the
+ *     kernel they depend on has finished and wait for it on counters in the
+ *     workspace (a bounded poll), so two factorisations must not share one
+ *     workspace while either is still running.  The helper streams and their events are shared by
  *     all calls of the process, so the entry points are not thread safe: calls
  *     from several host threads must be serialised by the caller.
  *   - Return value: DLA_SUCCESS (0); -i when the i-th argument (1-based) is

@@ -51,6 +51,27 @@ __device__ inline void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Hand-over between two kernels that run side by side on different streams: the producer's
+// threads make their stores visible device-wide and one of them bumps a counter; the consumer polls
+// the counter with one thread before it touches the data.  The consumer is launched early only to hide its
+// launch latency; the streams are arranged so that the producer never depends on the consumer, and
+// the poll is bounded: a consumer that gives up computes on stale data instead of hanging the GPU.
+__device__ inline void chain_signal(int* counter, int add, int tid) {
+  __threadfence();   // this thread's global stores, device scope
+  __syncthreads();   // every thread of the workgroup has fenced
+  if (tid == 0) __hip_atomic_fetch_add(counter, add, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void chain_wait(const int* counter, int target, int tid) {
+  if (tid == 0) {
+    for (int spins = 0; spins < (1 << 21); ++spins) {
+      if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+      __builtin_amdgcn_s_sleep(16);
+    }
+  }
+  __syncthreads();
+  __threadfence();   // acquire: loads below see what the producer published
+}
+
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator complex dies, workgroups are dealt round-robin
 
 // Workgroup id -> logical work item so that each XCD (and its private L2)

@@ -23,7 +23,7 @@ static size_t head_copy_bytes(dla_dtype dt) { return (size_t)kNbMax * kNbMax * (
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p) {
   (void)n;
   (void)p;
-  return 4 * inv_set_bytes(dt) + 4 * head_copy_bytes(dt);
+  return 4 * inv_set_bytes(dt) + 4 * head_copy_bytes(dt) + 256;  // + the hand-over counters of the latency chain
 }
 
 int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
@@ -128,7 +128,7 @@ static int launch_solve(SolveArgs<T> sa, hipStream_t st, hipEvent_t done = nullp
 }
 
 template <typename T, int KIND>
-static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done = nullptr) {
+static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done, int* workgroups) {
   auto kern = head_kernel<T, KIND>;
   constexpr int lds = head_lds_bytes<T, KIND>();
   static bool attr_done = false;
@@ -140,6 +140,7 @@ static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done = n
   }
   const int nt = (a.bn + kHeadTile - 1) / kHeadTile;
   const int grid = (KIND == KIND_LU) ? nt * nt : nt * (nt + 1) / 2;
+  *workgroups = grid;
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   launch_ev(kern, dim3((unsigned)grid), dim3(kHeadThreads), lds, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
@@ -148,17 +149,19 @@ static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done = n
 // Helper streams and events for look-ahead: library-owned, default priority, created on first use
 // and kept for the life of the process.
 struct LookaheadCtx {
+  hipStream_t head = nullptr;   // head updates
   hipStream_t panel = nullptr;  // panel solves + strip updates
   hipStream_t bulk = nullptr;   // bulk trailing updates
-  hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   bool ok = false;
 };
 static LookaheadCtx& lookahead_ctx() {
   static LookaheadCtx ctx;
   if (!ctx.ok) {
-    bool good = hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
+    bool good = hipStreamCreateWithFlags(&ctx.head, hipStreamNonBlocking) == hipSuccess &&
+                hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
-    for (int i = 0; i < 6 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 7 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
     ctx.ok = good;
   }
   return ctx;
@@ -197,6 +200,10 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     return reinterpret_cast<T*>(wsb + 4 * set + (size_t)(2 * (step & 1) + 1) * head_copy_bytes(dt));
   };
 
+  // hand-over counters of the look-ahead chain: [0] diagonal blocks factored, [1] head workgroups finished
+  int* const chain = reinterpret_cast<int*>(wsb + 4 * set + 4 * head_copy_bytes(dt));
+  bool chained = false;  // set by the look-ahead path
+  int heads_done = 0;    // head workgroups launched so far = what the next diagonal block waits for
   auto diag = [&](int64_t k0, int step, hipStream_t s, hipEvent_t done) -> int {
     DiagArgs<T> da;
     da.A = A + k0 * lda + k0;
@@ -206,6 +213,9 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     da.info = d_info;
     da.inv_lo = inv_lo_of(step);
     da.inv_up = inv_up_of(step);
+    da.wait_counter = chained ? chain + 1 : nullptr;  // head workgroups finished so far
+    da.wait_target = heads_done;
+    da.done_counter = chained ? chain : nullptr;
     return launch_diag<T, KIND>(da, s, done);
   };
   // panel solves of the block column / block row behind diagonal block k0
@@ -279,60 +289,55 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       if ((rc = trailing(Akk + (int64_t)b * lda, Akk + b, Akk + (int64_t)b * lda + b, m, b, 0, st, nullptr)) != DLA_SUCCESS) return rc;
     }
   } else {
-    // Look-ahead pipeline over three streams.  With N = block k+1 and N2 = block k+2:
-    //   caller's stream   diag(k) -> head(k): block (N,N) gets step k's update from the un-solved panel
-    //                     heads -> diag(k+1) -> ...        (the latency chain, nothing else on it)
+    // Look-ahead pipeline over four streams.  With N = block k+1 and N2 = block k+2:
+    //   caller's stream   diag(k): factor diagonal block k                 } the latency chain,
+    //   head stream       head(k): block (N,N) gets step k's update from   } nothing else on
+    //                     the un-solved panel heads                        } these two streams
     //   panel stream      solves(k): the full panel solves;  strips(k): step k's update of block
     //                     row N and block column N (what solves(k+1) reads) and of block (N2,N2)
     //                     (what head(k+1) reads)
     //   bulk stream       bulk(k): step k's update of everything behind block row/column N except
     //                     block (N2,N2)
-    // Dependencies beyond stream order: head(k) after strips(k-1); solves(k) after diag(k);
-    // strips(k) after bulk(k-1) (same memory); bulk(k) after solves(k).
+    // Dependencies: head(k) after diag(k) and strips(k-1); diag(k+1) after head(k); solves(k) after
+    // diag(k); strips(k) after bulk(k-1) (same memory); bulk(k) after solves(k).  Host order of a
+    // step: head(k), diag(k+1), solves(k), strips(k), bulk(k).
     // solves(k) overwrites the panel heads A[k][N], A[N][k] that head(k) reads, so strips(k-1), which
     // produces those two blocks, also writes a copy of them to the workspace and head(k) reads the
     // copies; only the first step reads them in place and makes solves(0) wait for head(0).
+    //
+    // The chain diag(k) -> head(k) -> diag(k+1) alternates between the caller's stream and the head
+    // stream, and each of its kernels is launched while its predecessor still runs: it waits for it
+    // on a counter in the workspace instead of a stream dependency, which hides its launch latency.
+    // Every kernel is submitted after everything it waits for, so the order of submission is a valid
+    // order of execution whatever hardware queues the streams share.
+    //
+    // Only the chain is handed over this way: a waiting kernel holds its compute units, and the
+    // bulk update needs every unit outside the reserve at once, so a head update that also waited
+    // in place for the strips (tried) doubled the bulk update's run time.
     LookaheadCtx& ctx = lookahead_ctx();
     if (!ctx.ok) return DLA_ERR_HIP;
-    hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_strip = ctx.ev[2], e_bulk = ctx.ev[3];
+    hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_bulk = ctx.ev[2], e_start = ctx.ev[3], e_strip = ctx.ev[6];
     hipEvent_t e_diag[2] = {ctx.ev[4], ctx.ev[5]};  // by step parity
-    bool strip_pending = false, bulk_pending = false;
     constexpr int SOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT;
+    const int nsteps = (int)((n + nb - 1) / nb) - 1;  // steps that have a panel behind the diagonal block
+    bool bulk_pending = false;
 
-    if ((rc = diag(0, 0, st, nullptr)) != DLA_SUCCESS) return rc;
-    int step = 0;
-    for (int64_t k0 = 0; k0 < n; k0 += nb, ++step) {
-      const int b = (int)((n - k0 < nb) ? n - k0 : nb);
+    // ---- panel and bulk streams of one step
+    auto panel_side = [&](int step) -> int {
+      const int64_t k0 = (int64_t)step * nb;
+      const int b = nb;  // only the last diagonal block can be short, and it has no panel
       const int64_t m = n - k0 - b;
-      if (m == 0) break;
       T* const Akk = A + k0 * lda + k0;
       T* const L21 = Akk + (int64_t)b * lda;  // m x b
       T* const U12 = Akk + b;                 // b x m   (LU)
       T* const A22 = L21 + b;
-      const int64_t bn = m < nb ? m : nb;       // size of block N
-      const int64_t mr = m - bn;                // what is left behind it
-      const int64_t bn2 = mr < nb ? mr : nb;    // size of block N2
-
-      // ---- caller's stream: head(k), diag(k+1)
-      if (strip_pending && hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
-      HeadArgs<T> ha;
-      ha.D = Akk;
-      ha.top = step == 0 ? U12 : head_top_of(step);
-      ha.side = step == 0 ? L21 : head_side_of(step);
-      ha.C = A22;
-      ha.lda = lda;
-      ha.ldh = step == 0 ? lda : kNbMax;
-      ha.b = b;
-      ha.bn = (int)bn;
-      ha.inv_lo = inv_lo_of(step);
-      ha.inv_up = inv_up_of(step);
-      if ((rc = launch_head<T, KIND>(ha, st, step == 0 ? e_head : nullptr)) != DLA_SUCCESS) return rc;
-      if ((rc = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return rc;
-
-      // ---- panel stream: solves(k), strips(k)
+      const int64_t bn = m < nb ? m : nb;     // size of block N
+      const int64_t mr = m - bn;              // what is left behind it
+      const int64_t bn2 = mr < nb ? mr : nb;  // size of block N2
+      int r;
       if (hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
       // the last kernel of the step on this stream carries e_strip
-      if ((rc = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return rc;
+      if ((r = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return r;
       if (mr > 0) {
         if (bulk_pending && hipStreamWaitEvent(ctx.panel, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
         const T* Lr = L21 + bn * lda;  // rows behind block N of the solved column panel
@@ -369,21 +374,61 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         {
           ProfileScope scope(PHASE_GEMM, flops, ctx.panel);
           tl_gemm_done_event = e_strip;
-          if ((rc = launch_gemm<T>(ps, SOP, g, ctx.panel)) != DLA_SUCCESS) return rc;
+          if ((r = launch_gemm<T>(ps, SOP, g, ctx.panel)) != DLA_SUCCESS) return r;
         }
       }
-      strip_pending = true;
-
-      // ---- bulk stream: bulk(k)
       if (mr > bn2) {
         if (hipStreamWaitEvent(ctx.bulk, e_solve, 0) != hipSuccess) return DLA_ERR_HIP;
-        if ((rc = trailing(L21 + bn * lda, U12 + bn, A22 + bn * lda + bn, mr, b, (int)bn2, ctx.bulk, e_bulk)) != DLA_SUCCESS)
-          return rc;
+        if ((r = trailing(L21 + bn * lda, U12 + bn, A22 + bn * lda + bn, mr, b, (int)bn2, ctx.bulk, e_bulk)) != DLA_SUCCESS)
+          return r;
         bulk_pending = true;
       }
+      return DLA_SUCCESS;
+    };
+
+    // ---- the chain of one step: head(k), diag(k+1)
+    auto chain_side = [&](int step) -> int {
+      const int64_t k0 = (int64_t)step * nb;
+      const int b = nb;
+      const int64_t m = n - k0 - b;
+      T* const Akk = A + k0 * lda + k0;
+      const int64_t bn = m < nb ? m : nb;
+      if (step > 0 && hipStreamWaitEvent(ctx.head, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
+      HeadArgs<T> ha;
+      ha.D = Akk;
+      ha.top = step == 0 ? Akk + b : head_top_of(step);
+      ha.side = step == 0 ? Akk + (int64_t)b * lda : head_side_of(step);
+      ha.C = Akk + (int64_t)b * lda + b;
+      ha.lda = lda;
+      ha.ldh = step == 0 ? lda : kNbMax;
+      ha.b = b;
+      ha.bn = (int)bn;
+      ha.inv_lo = inv_lo_of(step);
+      ha.inv_up = inv_up_of(step);
+      ha.wait_counter = chain;  // diagonal blocks factored: block k is number k + 1
+      ha.wait_target = step + 1;
+      ha.done_counter = chain + 1;
+      int head_wgs = 0, r;
+      if ((r = launch_head<T, KIND>(ha, ctx.head, e_head, &head_wgs)) != DLA_SUCCESS) return r;
+      heads_done += head_wgs;
+      if ((r = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return r;
+      return DLA_SUCCESS;
+    };
+
+    chained = true;
+    hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, chain, 2);
+    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    if (hipEventRecord(e_start, st) != hipSuccess || hipStreamWaitEvent(ctx.head, e_start, 0) != hipSuccess)
+      return DLA_ERR_HIP;
+    if ((rc = diag(0, 0, st, nullptr)) != DLA_SUCCESS) return rc;
+
+    for (int step = 0; step < nsteps; ++step) {
+      if ((rc = chain_side(step)) != DLA_SUCCESS) return rc;
+      if ((rc = panel_side(step)) != DLA_SUCCESS) return rc;
     }
     // join: everything the helper streams did becomes part of the caller's stream
-    if (strip_pending && hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
+    if (hipStreamWaitEvent(st, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
+    if (hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
     if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
   }
   if (KIND == KIND_CHOL && n > 1) {

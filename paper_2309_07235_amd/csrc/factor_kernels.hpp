@@ -253,6 +253,11 @@ struct DiagArgs {
   int* info;     // device, may be null
   T* inv_lo;     // out: nblk inverted 16 x 16 diagonal sub-blocks of L (row-major, 256 elements each)
   T* inv_up;     // out: same for U (LU only)
+  // look-ahead pipeline only (null / 0 otherwise): the block is ready once *wait_counter >= wait_target
+  // (head updates finished so far); on completion *done_counter is incremented
+  const int* wait_counter;
+  int wait_target;
+  int* done_counter;
 };
 
 template <typename T, int KIND>
@@ -270,6 +275,7 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
   const int bp = nblk * kIb;  // padded size: rows/columns b..bp-1 are identity
 
   DLA_TRACE(0);
+  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, tid);
   if (tid == 0) s_info = 0;
   // ---- load, padding with the identity: thread = two adjacent columns, 8 rows per pass, all
   // loads issued before the first LDS store
@@ -485,11 +491,17 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
     if (g.k0 == 0) *g.info = s_info;  // first block of the call: initialise
     else if (s_info != 0 && *g.info == 0) *g.info = s_info;
   }
+  if (g.done_counter) chain_signal(g.done_counter, 1, tid);
 }
 
 template <typename T>
 constexpr int diag_lds_bytes() {
   return ((kNbMax + 1) * kSld + kNbMax) * (int)sizeof(T);
+}
+
+// Zero a few ints (the hand-over counters) with a kernel: usable under stream capture, unlike a memset node.
+__global__ void zero_ints_kernel(int* p, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 
 // Zero the strict upper triangle (Cholesky output convention).

@@ -44,6 +44,11 @@ struct HeadArgs {
   int b, bn;        // b: multiple of 16, <= kNbMax;  1 <= bn <= kNbMax
   const T* inv_lo;  // inverted diagonal sub-blocks of the lower factor
   const T* inv_up;  // inverted diagonal sub-blocks of the upper factor (LU)
+  // D and the inverses are ready once *wait_counter >= wait_target (diagonal blocks factored so far);
+  // every workgroup increments *done_counter when its tile is stored
+  const int* wait_counter;
+  int wait_target;
+  int* done_counter;
 };
 
 template <typename T, int KIND>
@@ -162,6 +167,10 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
     }
   }
 
+  // The panel heads and the tile (requested above) do not depend on the diagonal block of this step,
+  // the factors below do: the kernel is launched while that block is still being factored.
+  chain_wait(g.wait_counter, g.wait_target, tid);
+
   // ---- stage the factors: one element per thread and sub-block, all loads before the first LDS store
   {
     const int rr = tid >> 4, cc = tid & 15;
@@ -207,7 +216,7 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
 #pragma unroll
     for (int v = 0; v < 4; ++v) slices[(wave * NB * 4 + s * 4 + v) * 64 + lane] = acc[s][v];
   __syncthreads();
-  if (!sub_on) return;
+  if (sub_on) {
   // C piece -= Y * X over k = 0 .. b-1.  Left operand: lane (l4, i) holds Y[i][k]; right operand:
   // lane (l4, n) holds X[k][n]; k = 16 * s + 4 * l4 + v for step (s, v) in both.
   // LU: Y slices come from waves 2, 3 and X slices from waves 0, 1.  Cholesky: rows from 0, 1, columns from 2, 3.
@@ -226,6 +235,8 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
     const int r = Mfma<T>::row_of(v, lane);
     if (r < rows_valid && l15 < cols_valid) Ct[(int64_t)r * lda + l15] = c[v];
   }
+  }
+  chain_signal(g.done_counter, 1, tid);
 }
 
 // --------------------------------------------------------------------------------------
