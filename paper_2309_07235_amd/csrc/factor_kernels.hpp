@@ -47,17 +47,18 @@ __device__ inline float row_bcast(float x) {
   return __builtin_amdgcn_update_dpp(x, x, 0x150 + K, 0xF, 0xF, true);
 }
 
-// acc += (value of src in lane K of the caller's 16-lane row) * m, as one DPP multiply-add.
+// acc -= (value of src in lane K of the caller's 16-lane row) * m, as one DPP multiply-add: the
+// negation is a source modifier of the instruction, so it adds nothing to a dependent chain.
 // The two wait states a DPP read needs after a VALU write of its source are part of the statement.
 template <int K>
-__device__ inline void fmac_bcast(double& acc, double src, double m) {
-  asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+__device__ inline void fnmac_bcast(double& acc, double src, double m) {
+  asm("s_nop 1\n\tv_fmac_f64_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
       : "+v"(acc)
       : "v"(src), "v"(m), "n"(K));
 }
 template <int K>
-__device__ inline void fmac_bcast(float& acc, float src, float m) {
-  asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+__device__ inline void fnmac_bcast(float& acc, float src, float m) {
+  asm("s_nop 1\n\tv_fmac_f32_dpp %0, -%1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
       : "+v"(acc)
       : "v"(src), "v"(m), "n"(K));
 }
@@ -132,27 +133,26 @@ __device__ inline void lu16(T (&a)[16], T (&rdiag)[16], int i, int& zero_at) {
     rdiag[k] = rp;
     const bool below = i > k;
     const T l = below ? a[k] * rp : T(0);
-    const T nl = -l;
     a[k] = below ? l : a[k];
     // Column k+1 first: it carries the next pivot, whose reciprocal (a chain of dependent
     // instructions) then overlaps with the independent updates of the remaining columns.
     if constexpr (k + 1 < 16) {
-      fmac_bcast<k>(a[k + 1], a[k + 1], nl);
+      fnmac_bcast<k>(a[k + 1], a[k + 1], l);
       piv = row_bcast<k + 1>(a[k + 1]);
       __builtin_amdgcn_sched_barrier(0);
       T r = rcp_estimate(piv);
       // interleave the Newton steps with the row updates, a few columns per step
       constexpr int rest = 14 - k;                 // columns k+2 .. 15
       constexpr int c1 = k + 2 + (rest + 3) / 4, c2 = k + 2 + (2 * rest + 3) / 4, c3 = k + 2 + (3 * rest + 3) / 4;
-      static_for<k + 2, c1>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<k>(a[j], a[j], nl); });
+      static_for<k + 2, c1>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<k>(a[j], a[j], l); });
       __builtin_amdgcn_sched_barrier(0);
       r = rcp_refine(piv, r);
-      static_for<c1, c2>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<k>(a[j], a[j], nl); });
+      static_for<c1, c2>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<k>(a[j], a[j], l); });
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (sizeof(T) == 8) r = rcp_refine(piv, r);
-      static_for<c2, c3>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<k>(a[j], a[j], nl); });
+      static_for<c2, c3>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<k>(a[j], a[j], l); });
       __builtin_amdgcn_sched_barrier(0);
-      static_for<c3, 16>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<k>(a[j], a[j], nl); });
+      static_for<c3, 16>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<k>(a[j], a[j], l); });
       rp = r;
     }
   });
@@ -173,27 +173,26 @@ __device__ inline void chol16(T (&a)[16], T (&rdiag)[16], int i, int& bad_at) {
     rdiag[k] = rs;
     const T l = (i == k) ? s : a[k] * rs;
     a[k] = (i >= k) ? l : a[k];
-    const T nak = -a[k];
     // rows i <= k only touch their scratch entries a[j], j > k >= i, below.
     // Column k+1 first (next pivot), then its reciprocal square root interleaved with the rest.
     if constexpr (k + 1 < 16) {
-      fmac_bcast<k + 1>(a[k + 1], a[k], nak);  // a[j] -= L[i][k] * L[j][k]; L[j][k] lives in lane j
+      fnmac_bcast<k + 1>(a[k + 1], a[k], a[k]);  // a[j] -= L[i][k] * L[j][k]; L[j][k] lives in lane j
       d = row_bcast<k + 1>(a[k + 1]);
       __builtin_amdgcn_sched_barrier(0);
       T y = rsq_estimate(d);
       constexpr int rest = 14 - k;
       constexpr int c1 = k + 2 + (rest + 3) / 4, c2 = k + 2 + (2 * rest + 3) / 4, c3 = k + 2 + (3 * rest + 3) / 4;
-      static_for<k + 2, c1>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<j>(a[j], a[k], nak); });
+      static_for<k + 2, c1>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<j>(a[j], a[k], a[k]); });
       __builtin_amdgcn_sched_barrier(0);
       y = rsq_refine(d, y);
-      static_for<c1, c2>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<j>(a[j], a[k], nak); });
+      static_for<c1, c2>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<j>(a[j], a[k], a[k]); });
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (sizeof(T) == 8) y = rsq_refine(d, y);
-      static_for<c2, c3>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<j>(a[j], a[k], nak); });
+      static_for<c2, c3>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<j>(a[j], a[k], a[k]); });
       __builtin_amdgcn_sched_barrier(0);
       T sq = d * y;
       sq = fma_t(fma_t(-sq, sq, d), T(0.5) * y, sq);
-      static_for<c3, 16>([&](auto jc) { constexpr int j = decltype(jc)::value; fmac_bcast<j>(a[j], a[k], nak); });
+      static_for<c3, 16>([&](auto jc) { constexpr int j = decltype(jc)::value; fnmac_bcast<j>(a[j], a[k], a[k]); });
       s = sq;
       rs = y;
     }
@@ -215,10 +214,10 @@ __device__ inline void inv_lower16(const T (&a)[16], const T (&rdiag)[16], T (&x
         x[j] *= scale;
       });
     }
-    const T nmult = (i > k) ? -a[k] : T(0);
+    const T mult = (i > k) ? a[k] : T(0);
     static_for<0, k + 1>([&](auto jc) {
       constexpr int j = decltype(jc)::value;
-      fmac_bcast<k>(x[j], x[j], nmult);
+      fnmac_bcast<k>(x[j], x[j], mult);
     });
   });
 }
@@ -235,10 +234,10 @@ __device__ inline void inv_upper16(const T (&a)[16], const T (&rdiag)[16], T (&x
       constexpr int j = decltype(jc)::value;
       x[j] *= scale;
     });
-    const T nmult = (i < k) ? -a[k] : T(0);
+    const T mult = (i < k) ? a[k] : T(0);
     static_for<k, 16>([&](auto jc) {
       constexpr int j = decltype(jc)::value;
-      fmac_bcast<k>(x[j], x[j], nmult);
+      fnmac_bcast<k>(x[j], x[j], mult);
     });
   });
 }
@@ -396,17 +395,16 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
       for (int i = 0; i < 16; ++i) x[i] = S[(o + i) * kSld + col];
       static_for<0, 15>([&](auto kc) {
         constexpr int k = decltype(kc)::value;
-        const T nxk = -x[k];
         static_for<k + 1, 16>([&](auto ic) {
           constexpr int i = decltype(ic)::value;
-          fmac_bcast<i>(x[i], f[k], nxk);  // x[i] -= L[i][k] * x[k]; L[i][k] = entry k of lane i
+          fnmac_bcast<i>(x[i], f[k], x[k]);  // x[i] -= L[i][k] * x[k]; L[i][k] = entry k of lane i
         });
         __builtin_amdgcn_sched_barrier(0);  // keep the broadcasts of later steps from being hoisted (registers)
       });
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[(o + i) * kSld + col] = x[i];
-    } else if (tid >= 256 && tid < 384) {
-      const int t = tid - 256;
+    } else if (tid >= 128 && tid < 256) {  // waves 2, 3: not the SIMDs of the row panel's waves 0, 1
+      const int t = tid - 128;
       const int row = t < rem ? o + kIb + t : kNbMax;  // dump row for the idle threads
       T f[16], x[16], rd[16];
 #pragma unroll
@@ -419,12 +417,11 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
       static_for<0, 16>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         x[j] *= rd[j];
-        const T nxj = -x[j];
         static_for<j + 1, 16>([&](auto qc) {
           constexpr int jj = decltype(qc)::value;
           // LU: U[j][jj] = entry jj of lane j;  Cholesky: (L^T)[j][jj] = L[jj][j] = entry j of lane jj
-          if constexpr (KIND == KIND_LU) fmac_bcast<j>(x[jj], f[jj], nxj);
-          else fmac_bcast<jj>(x[jj], f[j], nxj);
+          if constexpr (KIND == KIND_LU) fnmac_bcast<j>(x[jj], f[jj], x[j]);
+          else fnmac_bcast<jj>(x[jj], f[j], x[j]);
         });
         __builtin_amdgcn_sched_barrier(0);
       });
