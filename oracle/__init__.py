@@ -1,4 +1,4 @@
-"""CPU oracle (test infrastructure only) for 3mm, LU without pivoting and Cholesky.
+"""CPU oracle (test infrastructure only) for 3mm, LU without pivoting, Cholesky, and solves with the factors.
 
 The arithmetic lives in ``dla_oracle.c`` (plain fp64 loop nests that follow the
 problem statements in the paper's Section "Linear Algebra Benchmarks").  This
@@ -57,6 +57,10 @@ def _load():
     lib.oracle_cholesky_apply.argtypes = [dp, i64, i64, dp, dp, dp]
     lib.oracle_matvec.argtypes = [dp, i64, i64, i64, dp, dp]
     lib.oracle_symv_lower.argtypes = [dp, i64, i64, dp, dp]
+    lib.oracle_lu_solve.argtypes = [dp, i64, i64, dp, i64, i64]
+    lib.oracle_lu_solve.restype = None
+    lib.oracle_cholesky_solve.argtypes = [dp, i64, i64, dp, i64, i64]
+    lib.oracle_cholesky_solve.restype = None
     _lib = lib
     return lib
 
@@ -169,3 +173,31 @@ def symv_lower(A, x):
     y = np.empty(A.shape[0])
     _load().oracle_symv_lower(_p(A), A.shape[1], A.shape[0], _p(x), _p(y))
     return y
+
+
+def _rhs(B, n: int):
+    b = np.array(B, dtype=np.float64, order="C", copy=True)
+    vec = b.ndim == 1
+    if vec:
+        b = b.reshape(n, 1)
+    if b.ndim != 2 or b.shape[0] != n:
+        raise ValueError("B must have as many rows as the factor")
+    return b, vec
+
+
+def lu_solve(LU, B):
+    """X with (L*U)*X = B, from an in-place LU result: forward substitution with unit-lower L, backward with U."""
+    LU = _dense(LU, "LU")
+    n = LU.shape[0]
+    b, vec = _rhs(B, n)
+    _load().oracle_lu_solve(_p(LU), n, LU.shape[1], _p(b), b.shape[1], b.shape[1])
+    return b[:, 0] if vec else b
+
+
+def cholesky_solve(L, B):
+    """X with (L*L^T)*X = B, from the lower triangle of L: forward with L, backward with L^T."""
+    L = _dense(L, "L")
+    n = L.shape[0]
+    b, vec = _rhs(B, n)
+    _load().oracle_cholesky_solve(_p(L), n, L.shape[1], _p(b), b.shape[1], b.shape[1])
+    return b[:, 0] if vec else b

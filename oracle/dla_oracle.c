@@ -1,7 +1,8 @@
 /*
  * CPU oracle for the three dense kernels of the paper's case study (Section
  * "Linear Algebra Benchmarks"): 3mm  G = (A*B)*(C*D), LU decomposition without
- * pivoting  A = L*U, and Cholesky decomposition  A = L*L^T.
+ * pivoting  A = L*U, and Cholesky decomposition  A = L*L^T; and for solving
+ * A*X = B with those factors by forward and backward substitution.
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU
  * library is checked against.  It shares no code, header, table or helper with
@@ -244,5 +245,49 @@ void oracle_symv_lower(const double *a, int64_t ld, int64_t n, const double *x, 
         for (int64_t j = 0; j <= i; ++j) s += a[IDX(i, j, ld)] * x[j];
         for (int64_t j = i + 1; j < n; ++j) s += a[IDX(j, i, ld)] * x[j];
         y[i] = s;
+    }
+}
+
+/*
+ * Solving A*X = B with the factors (the use the paper names for both
+ * decompositions, Section "Linear Algebra Benchmarks": systems of linear
+ * equations).  B is n x nrhs, row-major, overwritten by X; every column is an
+ * independent system, so the column loop carries the OpenMP pragma and each
+ * column's sums are added in a fixed order.
+ *
+ *   LU:        L*y = b forward (unit diagonal: no division), then U*x = y backward.
+ *   Cholesky:  L*y = b forward, then L^T*x = y backward (lower triangle of l only).
+ */
+void oracle_lu_solve(const double *lu, int64_t n, int64_t ld, double *b, int64_t nrhs, int64_t ldb)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < nrhs; ++c) {
+        for (int64_t i = 0; i < n; ++i) {
+            double s = b[IDX(i, c, ldb)];
+            for (int64_t j = 0; j < i; ++j) s -= lu[IDX(i, j, ld)] * b[IDX(j, c, ldb)];
+            b[IDX(i, c, ldb)] = s;
+        }
+        for (int64_t i = n - 1; i >= 0; --i) {
+            double s = b[IDX(i, c, ldb)];
+            for (int64_t j = i + 1; j < n; ++j) s -= lu[IDX(i, j, ld)] * b[IDX(j, c, ldb)];
+            b[IDX(i, c, ldb)] = s / lu[IDX(i, i, ld)];
+        }
+    }
+}
+
+void oracle_cholesky_solve(const double *l, int64_t n, int64_t ld, double *b, int64_t nrhs, int64_t ldb)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < nrhs; ++c) {
+        for (int64_t i = 0; i < n; ++i) {
+            double s = b[IDX(i, c, ldb)];
+            for (int64_t j = 0; j < i; ++j) s -= l[IDX(i, j, ld)] * b[IDX(j, c, ldb)];
+            b[IDX(i, c, ldb)] = s / l[IDX(i, i, ld)];
+        }
+        for (int64_t i = n - 1; i >= 0; --i) {
+            double s = b[IDX(i, c, ldb)];
+            for (int64_t j = i + 1; j < n; ++j) s -= l[IDX(j, i, ld)] * b[IDX(j, c, ldb)];
+            b[IDX(i, c, ldb)] = s / l[IDX(i, i, ld)];
+        }
     }
 }

@@ -5,7 +5,8 @@ The oracle is checked against things other than itself: hand-worked fixtures
 exact-integer matrices with known factors, invariants that tie LU to Cholesky,
 brute-force 4-index sums for 3mm, exact rational elimination on tiny inputs,
 and library routines on special cases (numpy's Cholesky; a pivoted library LU
-on matrices where no row swap occurs).
+on matrices where no row swap occurs; the library's triangular and dense
+solvers for the substitutions with the factors).
 """
 import json
 import math
@@ -344,3 +345,109 @@ def test_generators_are_counter_based_and_seeded():
     Ai = inputs.integer_matrix(3, 0, 40, 40)
     assert np.array_equal(Ai, np.round(Ai)) and Ai.min() >= -3 and Ai.max() <= 3
     assert len(np.unique(Ai)) == 7
+
+
+# ---------------------------------------------------------------- solving with the factors
+def test_solve_fixtures_are_exact_and_reproduced(oracle, golden):
+    """Hand-worked systems: the stored X satisfies (L*U)*X == B resp. (L*L^T)*X == B exactly, and the
+    oracle returns it bit for bit (all intermediate values are small integers)."""
+    for c in golden["lu_solve"]:
+        LU, B, X = _frac(c["LU"]), _frac(c["B"]), _frac(c["X"])
+        n = len(LU)
+        L = [[LU[i][j] if j < i else Fraction(int(i == j)) for j in range(n)] for i in range(n)]
+        U = [[LU[i][j] if j >= i else Fraction(0) for j in range(n)] for i in range(n)]
+        assert _fmul(_fmul(L, U), X) == B, c["name"]
+        assert np.array_equal(oracle.lu_solve(_tofloat(c["LU"]), _tofloat(c["B"])), _tofloat(c["X"])), c["name"]
+    for c in golden["cholesky_solve"]:
+        L, B, X = _frac(c["L"]), _frac(c["B"]), _frac(c["X"])
+        n = len(L)
+        LT = [[L[j][i] for j in range(n)] for i in range(n)]
+        assert _fmul(_fmul(L, LT), X) == B, c["name"]
+        assert np.array_equal(oracle.cholesky_solve(_tofloat(c["L"]), _tofloat(c["B"])), _tofloat(c["X"])), c["name"]
+
+
+def test_lu_solve_ignores_the_stored_diagonal_in_the_forward_pass(oracle):
+    """The diagonal of an in-place LU result belongs to U: dividing by it in the forward pass, or using L's
+    implied ones in the backward pass, changes the 3x3 fixture's answer."""
+    LU = np.array([[4.0, 1.0, 2.0], [2.0, 3.0, -3.0], [3.0, 2.0, 10.0]])
+    b = np.array([12.0, 21.0, 60.0])
+    x = oracle.lu_solve(LU, b)
+    assert np.array_equal(x, [1.0, 2.0, 3.0])
+    L = np.tril(LU, -1) + np.eye(3)
+    U = np.triu(LU)
+    wrong_forward = np.linalg.solve(U, np.linalg.solve(np.tril(LU), b))          # divided by U's diagonal
+    wrong_backward = np.linalg.solve(np.triu(LU, 1) + np.eye(3), np.linalg.solve(L, b))  # unit U
+    assert not np.allclose(x, wrong_forward) and not np.allclose(x, wrong_backward)
+
+
+def test_cholesky_solve_uses_the_transpose_in_the_backward_pass(oracle):
+    L = np.array([[2.0, 0.0, 0.0], [1.0, 3.0, 0.0], [-1.0, 2.0, 1.0]])
+    b = np.array([6.0, 27.0, 14.0])
+    x = oracle.cholesky_solve(L, b)
+    assert np.array_equal(x, [1.0, 2.0, 1.0])
+    forward_twice = np.linalg.solve(L, np.linalg.solve(L, b))
+    assert not np.allclose(x, forward_twice)
+    # only the lower triangle is read
+    junk = L + np.triu(np.full((3, 3), 7.0), 1)
+    assert np.array_equal(oracle.cholesky_solve(junk, b), x)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_lu_solve_against_exact_rational_solution(oracle, seed):
+    n, nrhs = 6, 3
+    Ai = inputs.integer_matrix(seed, 3, n, n, -4, 4) + 9 * np.eye(n)
+    Bi = inputs.integer_matrix(seed, 4, n, nrhs, -5, 5)
+    A = _frac(Ai.astype(int).tolist())
+    L, U = _rational_lu(A)
+    # exact solution by substitution in rationals
+    X = [[Fraction(0)] * nrhs for _ in range(n)]
+    for c in range(nrhs):
+        y = [Fraction(0)] * n
+        for i in range(n):
+            y[i] = Fraction(int(Bi[i, c])) - sum(L[i][j] * y[j] for j in range(i))
+        for i in reversed(range(n)):
+            X[i][c] = (y[i] - sum(U[i][j] * X[j][c] for j in range(i + 1, n))) / U[i][i]
+    assert _fmul(A, X) == _frac(Bi.astype(int).tolist())
+    lu, info = oracle.lu(Ai)
+    assert info == 0
+    got = oracle.lu_solve(lu, Bi)
+    np.testing.assert_allclose(got, _tofloat(X), rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("n,nrhs", [(1, 1), (40, 1), (129, 7)])
+def test_solves_match_library_routines(oracle, n, nrhs):
+    scipy_linalg = pytest.importorskip("scipy.linalg")
+    A = inputs.general_dominant_matrix(n, 6)
+    S = inputs.spd_matrix(n, 7)
+    B = inputs.uniform_matrix(8, 1, n, nrhs)
+    lu, info = oracle.lu(A)
+    assert info == 0
+    X = oracle.lu_solve(lu, B)
+    assert max_rel_err(X, np.linalg.solve(A, B)) < 1e-11
+    # the two substitutions one at a time, with the library's triangular solver on the same factors
+    Y = scipy_linalg.solve_triangular(lu, B, lower=True, unit_diagonal=True)
+    assert max_rel_err(X, scipy_linalg.solve_triangular(lu, Y, lower=False)) < 1e-12
+    Lc, info = oracle.cholesky(S)
+    assert info == 0
+    Xc = oracle.cholesky_solve(Lc, B)
+    assert max_rel_err(Xc, scipy_linalg.cho_solve((Lc, True), B)) < 1e-12
+    assert max_rel_err(Xc, np.linalg.solve(S, B)) < 1e-10
+
+
+def test_solve_invariants(oracle):
+    n, nrhs = 50, 4
+    A = inputs.general_dominant_matrix(n, 9)
+    B = inputs.uniform_matrix(9, 2, n, nrhs)
+    lu, _ = oracle.lu(A)
+    X = oracle.lu_solve(lu, B)
+    assert np.abs(A @ X - B).max() <= 64 * n * EPS64 * np.abs(A).max() * np.abs(X).max()
+    # columns are independent systems: solving them one at a time gives the same bits
+    for c in range(nrhs):
+        assert np.array_equal(oracle.lu_solve(lu, B[:, c]), X[:, c])
+    # identity and diagonal factors
+    assert np.array_equal(oracle.lu_solve(np.eye(n), B), B)
+    d = np.arange(1.0, n + 1.0)
+    assert np.array_equal(oracle.lu_solve(np.diag(d), B), B / d[:, None])
+    np.testing.assert_allclose(oracle.cholesky_solve(np.diag(d), B), B / (d * d)[:, None], rtol=4 * EPS64)
+    with pytest.raises(ValueError):
+        oracle.lu_solve(lu, B[:-1])
