@@ -117,6 +117,28 @@ int lu_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_
 int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p,
                     void* d_workspace, size_t workspace_bytes, void* hip_stream, int* d_info);
 
+/*
+ * Solving A*X = B with the factors (same Section: both decompositions are introduced as the way
+ * to solve systems of linear equations).  lu_solve: L*Y = B by forward substitution (unit diagonal),
+ * then U*X = Y backward.  cholesky_solve: L*Y = B, then L^T*X = Y (only the lower triangle is read).
+ *   d_lu / d_l   device, n x n, leading dimension lda: the output of lu_factor / cholesky_factor;
+ *                read only.
+ *   d_b          device, n x nrhs, row-major with leading dimension ldb (every column is one
+ *                right-hand side); overwritten by X.  Must not overlap the factor.
+ *   d_workspace / workspace_bytes   device scratch of at least solve_workspace_bytes(n, dt) bytes,
+ *                256-byte aligned: the diagonal blocks of the factor prepared for the two
+ *                substitutions (about 1.3 KB per row of the factor in fp64).
+ * n == 0 or nrhs == 0 is a successful no-op that needs no workspace.  A zero on the factor's diagonal
+ * gives infinities or NaNs in X; nothing is reported (the factorisation's d_info already said so).
+ */
+int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+             void* d_workspace, size_t workspace_bytes, void* hip_stream);
+int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+                   void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Scratch bytes lu_solve / cholesky_solve need (same for both). 0 on invalid arguments. */
+size_t solve_workspace_bytes(int64_t n, dla_dtype dt);
+
 /* Scratch bytes lu_factor / cholesky_factor need (same for both). 0 on invalid arguments. */
 size_t factor_workspace_bytes(int64_t n, dla_dtype dt, const dla_factor_params* p);
 
@@ -146,6 +168,9 @@ size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt);
  *          above the diagonal are skipped, the upper part of diagonal tiles
  *          is computed too (the Cholesky trailing update)
  *   op 3:  C -= A*B^T          A m x k, B n x k, every tile (the Cholesky look-ahead panel update)
+ *   op 4:  C -= A^T*B          A k x m, B k x n (the backward pass of cholesky_solve multiplies by
+ *          L^T this way); only the 32x32 (16x16 waves) and 64x64 (32x32 waves) macro-tiles, p == NULL
+ *          takes the latter
  * C must not overlap A or B.
  */
 int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c,

@@ -61,6 +61,12 @@ def _load() -> ctypes.CDLL:
     lib.lu_factor.restype = ci
     lib.cholesky_factor.argtypes = lib.lu_factor.argtypes
     lib.cholesky_factor.restype = ci
+    lib.lu_solve.argtypes = [vp, i64, i64, vp, i64, i64, ci, vp, sz, vp]
+    lib.solve_workspace_bytes.argtypes = [i64, ci]
+    lib.solve_workspace_bytes.restype = sz
+    lib.lu_solve.restype = ci
+    lib.cholesky_solve.argtypes = lib.lu_solve.argtypes
+    lib.cholesky_solve.restype = ci
     lib.factor_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(FactorParams)]
     lib.factor_workspace_bytes.restype = sz
     lib.mm3.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i64, i64, i64, ci,
@@ -202,6 +208,36 @@ def cholesky_factor(a, p: FactorParams | None = None, workspace=None, info=None,
     return _factor(lib.cholesky_factor, "cholesky_factor", a, p, workspace, info, stream)
 
 
+def solve_workspace_bytes(n: int, dt: int) -> int:
+    return int(lib.solve_workspace_bytes(n, dt))
+
+
+def _solve(fn, name: str, f, b, workspace, stream):
+    n = f.shape[0]
+    if f.ndim != 2 or f.shape[1] != n:
+        raise ValueError(f"{name}: the factor must be square")
+    if b.ndim != 2 or b.shape[0] != n:
+        raise ValueError(f"{name}: b must be a matrix with as many rows as the factor")
+    dt = _dtype_code(f)
+    if _dtype_code(b) != dt:
+        raise ValueError(f"{name}: factor and right-hand sides differ in dtype")
+    (fp, ldf), (bp, ldb) = _matrix(f, "factor"), _matrix(b, "b")
+    ws, wsp, wsb = _workspace(solve_workspace_bytes(n, dt), f.device, workspace)
+    _check(fn(fp, n, ldf, bp, b.shape[1], ldb, dt, wsp, wsb, ctypes.c_void_p(_stream_ptr(stream))), name)
+    return ws
+
+
+def lu_solve(lu, b, workspace=None, stream=None):
+    """Overwrites the device matrix b (n x nrhs) with X, (L*U)*X = b, from lu_factor's output (see dla.h: lu_solve).
+    Returns the workspace it used (pass it back in to avoid the allocation)."""
+    return _solve(lib.lu_solve, "lu_solve", lu, b, workspace, stream)
+
+
+def cholesky_solve(l, b, workspace=None, stream=None):
+    """Overwrites b with X, (L*L^T)*X = b, from cholesky_factor's output (see dla.h: cholesky_solve)."""
+    return _solve(lib.cholesky_solve, "cholesky_solve", l, b, workspace, stream)
+
+
 def mm3(a, b, c, d, g, p: Mm3Params | None = None, workspace=None, stream=None):
     """G = (A*B)*(C*D) on device tensors; g is overwritten (see dla.h: mm3)."""
     ni, nk = a.shape
@@ -220,8 +256,9 @@ def mm3(a, b, c, d, g, p: Mm3Params | None = None, workspace=None, stream=None):
 
 
 def dla_gemm(op: int, a, b, c, p: GemmParams | None = None, stream=None):
-    """c (op)= a*b with op 0: assign, 1: subtract, 2: lower(c) -= a*b^T (see dla.h: dla_gemm)."""
-    m, k = a.shape
+    """c (op)= a*b with op 0: assign, 1: subtract, 2: lower(c) -= a*b^T, 3: c -= a*b^T, 4: c -= a^T*b
+    (see dla.h: dla_gemm)."""
+    m, k = (a.shape[1], a.shape[0]) if op == 4 else a.shape
     n = c.shape[1]
     dt = _dtype_code(a)
     (ap, lda), (bp, ldb), (cp, ldc) = _matrix(a, "a"), _matrix(b, "b"), _matrix(c, "c")

@@ -319,7 +319,7 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
 
 int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb, void* d_c, int64_t ldc, int64_t m,
              int64_t n, int64_t k, dla_dtype dt, const dla_gemm_params* p, void* hip_stream) {
-  if (op < OP_ASSIGN || op > OP_SUB_NT) return -1;
+  if (op < OP_ASSIGN || op > OP_SUB_TN) return -1;
   if (m < 0) return -8;
   if (n < 0) return -9;
   if (k < 0) return -10;
@@ -330,7 +330,7 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   if (!empty && k > 0 && !d_a) return -2;
   if (!empty && k > 0 && !d_b) return -4;
   if (!empty && !d_c) return -6;
-  if (lda < (k > 0 ? k : 1)) return -3;
+  if (lda < (op == OP_SUB_TN ? (m > 0 ? m : 1) : (k > 0 ? k : 1))) return -3;
   if (ldb < ((op == OP_SUB_NT_LOWER || op == OP_SUB_NT) ? (k > 0 ? k : 1) : (n > 0 ? n : 1))) return -5;
   if (ldc < (n > 0 ? n : 1)) return -7;
   const size_t es = (size_t)esize(dt);
@@ -339,6 +339,11 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   GemmSchedule s;
   int rc = resolve_schedule(dt, p, op, &s, m, n);
   if (rc != DLA_SUCCESS) return rc;
+  if (op == OP_SUB_TN) {  // instantiated for the 32x32 (16x16 waves) and 64x64 (32x32 waves) macro-tiles only
+    if (!p || (p->tile_m == 0 && p->tile_n == 0)) s = GemmSchedule{64, 64, 16, 2, 32, 32};
+    const bool ok = (s.tm == 32 && s.tn == 32 && s.wm == 16 && s.wn == 16) || (s.tm == 64 && s.tn == 64 && s.wm == 32 && s.wn == 32);
+    if (!ok) return DLA_ERR_UNSUPPORTED_PARAMS;
+  }
   if (empty) return DLA_SUCCESS;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (k == 0) {
@@ -457,6 +462,44 @@ int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_f
   if (dt == DLA_F64)
     return cholesky_factor_impl<double>((double*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
   return cholesky_factor_impl<float>((float*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
+}
+
+static int solve_common_checks(const void* d_f, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb,
+                               dla_dtype dt) {
+  if (n < 0) return -2;
+  if (nrhs < 0) return -5;
+  if (dt != DLA_F64 && dt != DLA_F32) return -7;
+  if (n > 0 && (!d_f || ((uintptr_t)d_f % (size_t)esize(dt)))) return -1;
+  if (lda < (n > 0 ? n : 1)) return -3;
+  if (n > 0 && nrhs > 0 && (!d_b || ((uintptr_t)d_b % (size_t)esize(dt)))) return -4;
+  if (ldb < (nrhs > 0 ? nrhs : 1)) return -6;
+  if (n > kMaxDim || nrhs > kMaxDim) return DLA_ERR_TOO_LARGE;
+  return DLA_SUCCESS;
+}
+
+size_t solve_workspace_bytes(int64_t n, dla_dtype dt) {
+  if (n < 0 || n > kMaxDim || (dt != DLA_F64 && dt != DLA_F32)) return 0;
+  return solve_workspace_bytes_impl(n, dt);
+}
+
+int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+             void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = solve_common_checks(d_lu, n, lda, d_b, nrhs, ldb, dt);
+  if (rc != DLA_SUCCESS) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return solve_impl<double, 0>((const double*)d_lu, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
+  return solve_impl<float, 0>((const float*)d_lu, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
+}
+
+int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+                   void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = solve_common_checks(d_l, n, lda, d_b, nrhs, ldb, dt);
+  if (rc != DLA_SUCCESS) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return solve_impl<double, 1>((const double*)d_l, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
+  return solve_impl<float, 1>((const float*)d_l, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
 }
 
 int dla_profile_enable(int on) {

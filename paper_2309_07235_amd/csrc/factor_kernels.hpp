@@ -497,7 +497,7 @@ constexpr int diag_lds_bytes() {
 }
 
 // Zero a few ints (the hand-over counters) with a kernel: usable under stream capture, unlike a memset node.
-__global__ void zero_ints_kernel(int* p, int n) {
+static __global__ void zero_ints_kernel(int* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 

@@ -12,14 +12,17 @@
 // LDS layouts.  A rows keep k contiguous with an odd row stride (TK+1): the
 // 16 lanes that read one fragment column then hit 16 distinct bank pairs.
 // B (k x n) keeps n contiguous: a fragment row is one contiguous 128-byte run.
-// For the A*B^T forms the right operand is stored like A.
+// For the A*B^T forms the right operand is stored like A; for the A^T*B form the left operand
+// (k x m in memory) is stored like B.
 #pragma once
 #include <type_traits>
 #include "dla_common.hpp"
 
 namespace dla {
 
-enum GemmOp { OP_ASSIGN = 0, OP_SUB = 1, OP_SUB_NT_LOWER = 2, OP_SUB_NT = 3 };
+// OP_SUB_TN: C -= A^T * B with A stored k x m (the Cholesky backward substitution multiplies by L^T
+// without forming it); instantiated for the two small macro-tiles only.
+enum GemmOp { OP_ASSIGN = 0, OP_SUB = 1, OP_SUB_NT_LOWER = 2, OP_SUB_NT = 3, OP_SUB_TN = 4 };
 
 template <typename T>
 struct GemmProblem {
@@ -43,11 +46,11 @@ struct GemmGroup {
   int total_tiles;
 };
 
-template <int TM, int TN, int TK, int WM, int WN, bool BT, int ESZ>
+template <int TM, int TN, int TK, int WM, int WN, bool BT, int ESZ, bool AT = false>
 struct GemmLds {
-  static constexpr int SA = TK + 1;
+  static constexpr int SA = AT ? TM : TK + 1;
   static constexpr int SB = BT ? TK + 1 : TN;
-  static constexpr int A_ELEMS = TM * SA;
+  static constexpr int A_ELEMS = AT ? TK * SA : TM * SA;
   static constexpr int B_ELEMS_RAW = BT ? TN * SB : TK * SB;
   // keep every buffer 16-byte aligned
   static constexpr int ALIGN_E = 16 / ESZ;
@@ -164,7 +167,7 @@ struct ColTileLoader {
       r[it][1] = q[c1[it]];
     }
   }
-  template <int STRIDE, bool MASK>
+  template <int STRIDE, bool MASK, bool NEGATE = false>
   __device__ inline void store(T* __restrict__ s, int tid, int k_valid) const {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
@@ -176,8 +179,8 @@ struct ColTileLoader {
           x0 = (ok0[it] && kr < k_valid) ? x0 : T(0);
           x1 = (ok1[it] && kr < k_valid) ? x1 : T(0);
         }
-        s[kr * STRIDE + 2 * c2] = x0;
-        s[kr * STRIDE + 2 * c2 + 1] = x1;
+        s[kr * STRIDE + 2 * c2] = NEGATE ? -x0 : x0;
+        s[kr * STRIDE + 2 * c2 + 1] = NEGATE ? -x1 : x1;
       }
     }
   }
@@ -195,7 +198,8 @@ gemm_kernel(const GemmGroup<T> g) {
   constexpr bool BT = (OP == OP_SUB_NT_LOWER || OP == OP_SUB_NT);
   constexpr bool LOWER = (OP == OP_SUB_NT_LOWER);
   constexpr bool SUB = (OP != OP_ASSIGN);
-  using L = GemmLds<TM, TN, TK, WM, WN, BT, (int)sizeof(T)>;
+  constexpr bool AT = (OP == OP_SUB_TN);
+  using L = GemmLds<TM, TN, TK, WM, WN, BT, (int)sizeof(T), AT>;
   using acc_t = typename Mfma<T>::acc_t;
 
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -266,13 +270,15 @@ gemm_kernel(const GemmGroup<T> g) {
 
   // ---- main loop -----------------------------------------------------------------
   RowTileLoader<T, TM, TK, NT> la;
+  ColTileLoader<T, TK, TM, NT> lat;   // left operand when it is k x m (AT)
   RowTileLoader<T, TN, TK, NT> lbt;   // right operand when it is n x k (BT)
   ColTileLoader<T, TK, TN, NT> lbn;   // right operand when it is k x n
-  const T* const Ag = P.A + (int64_t)m0 * lda;
+  const T* const Ag = AT ? P.A + m0 : P.A + (int64_t)m0 * lda;
   const T* const Bg = BT ? P.B + (int64_t)n0 * ldb : P.B + n0;
   const int nslab = (K + TK - 1) / TK;
 
-  la.init(Ag, lda, tid, M - m0);
+  if (AT) lat.init(Ag, lda, tid, M - m0);
+  else la.init(Ag, lda, tid, M - m0);
   if (BT) lbt.init(Bg, ldb, tid, N - n0);
   else lbn.init(Bg, ldb, tid, N - n0);
   // Two copies of the pipeline, chosen per slab: interior slabs (whole tile inside the matrix, whole
@@ -281,11 +287,13 @@ gemm_kernel(const GemmGroup<T> g) {
   auto fetch = [&](auto edge, int s) {
     const int k0 = s * TK;
     if constexpr (!decltype(edge)::value) {
-      la.load_full(k0);
+      if (AT) lat.load_full(k0, tid);
+      else la.load_full(k0);
       if (BT) lbt.load_full(k0);
       else lbn.load_full(k0, tid);
     } else {
-      la.load_edge(k0, K - k0, tid);
+      if (AT) lat.load_edge(k0, K - k0, tid);
+      else la.load_edge(k0, K - k0, tid);
       if (BT) lbt.load_edge(k0, K - k0, tid);
       else lbn.load_edge(k0, K - k0, tid);
     }
@@ -295,7 +303,8 @@ gemm_kernel(const GemmGroup<T> g) {
     T* sa = smem + buf * L::STAGE;
     T* sb = sa + L::A_PAD;
     const int kv = K - s * TK;
-    la.template store<SUB, L::SA, E>(sa, tid, kv);  // subtracting forms multiply by -A
+    if (AT) lat.template store<L::SA, E, SUB>(sa, tid, kv);
+    else la.template store<SUB, L::SA, E>(sa, tid, kv);  // subtracting forms multiply by -A
     if (BT) lbt.template store<false, L::SB, E>(sb, tid, kv);
     else lbn.template store<L::SB, E>(sb, tid, kv);
   };
@@ -306,13 +315,13 @@ gemm_kernel(const GemmGroup<T> g) {
       if (more) fetch(edge, s + 1);
       const T* sa = smem + (s & 1) * L::STAGE;
       const T* sb = sa + L::A_PAD;
-      const T* pa = sa + (wm0 + l15) * L::SA + l4;
+      const T* pa = AT ? sa + l4 * L::SA + wm0 + l15 : sa + (wm0 + l15) * L::SA + l4;
       const T* pb = BT ? sb + (wn0 + l15) * L::SB + l4 : sb + l4 * L::SB + wn0 + l15;
 #pragma unroll UK
       for (int kk = 0; kk < KSTEPS; ++kk) {
         T fa[FM], fb[FN];
 #pragma unroll
-        for (int a = 0; a < FM; ++a) fa[a] = pa[a * 16 * L::SA + kk * 4];
+        for (int a = 0; a < FM; ++a) fa[a] = AT ? pa[kk * 4 * L::SA + a * 16] : pa[a * 16 * L::SA + kk * 4];
 #pragma unroll
         for (int b = 0; b < FN; ++b) fb[b] = BT ? pb[b * 16 * L::SB + kk * 4] : pb[kk * 4 * L::SB + b * 16];
 #pragma unroll

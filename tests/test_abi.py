@@ -26,7 +26,8 @@ def _declared_functions():
 
 def test_header_declares_the_boundary():
     names = _declared_functions()
-    for must in ("lu_factor", "cholesky_factor", "mm3", "mm3_workspace_bytes", "factor_workspace_bytes",
+    for must in ("lu_factor", "cholesky_factor", "lu_solve", "cholesky_solve", "mm3", "mm3_workspace_bytes",
+                 "factor_workspace_bytes",
                  "dla_gemm", "dla_enumerate_tiles", "dla_gemm_params_supported", "dla_default_params",
                  "dla_strerror"):
         assert must in names
@@ -131,6 +132,26 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert mm3(p=ctypes.byref(badp)) == B.DLA_ERR_UNSUPPORTED_PARAMS
     assert mm3(dims=(0, 8, 8, 8, 8), a=None, g=None, ws=None, wsb=0) == 0  # empty G: nothing to do
 
+    for solve in (L.lu_solve, L.cholesky_solve):
+        assert solve(None, 8, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -1
+        assert solve(vp(0x1004), 8, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -1  # misaligned
+        assert solve(fake, -1, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -2
+        assert solve(fake, 8, 7, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -3
+        assert solve(fake, 8, 8, None, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -4
+        assert solve(fake, 8, 8, fake, -2, 2, B.DLA_F64, fake, 1 << 20, None) == -5
+        assert solve(fake, 8, 8, fake, 3, 2, B.DLA_F64, fake, 1 << 20, None) == -6
+        assert solve(fake, 8, 8, fake, 2, 2, 7, fake, 1 << 20, None) == -7
+        assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, None, 0, None) == B.DLA_ERR_WORKSPACE
+        assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, fake, 64, None) == B.DLA_ERR_WORKSPACE
+        assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, vp(0x1008), 1 << 20, None) == B.DLA_ERR_WORKSPACE
+        assert solve(None, 0, 1, None, 2, 2, B.DLA_F64, None, 0, None) == 0  # nothing to solve
+        assert solve(fake, 8, 8, None, 0, 1, B.DLA_F64, None, 0, None) == 0  # no right-hand side
+    assert L.solve_workspace_bytes(4000, B.DLA_F64) == 2 * 32 * 36 * 16 * 17 * 8
+    assert L.solve_workspace_bytes(1, B.DLA_F32) == 2 * 36 * 16 * 17 * 4
+    assert L.solve_workspace_bytes(-1, B.DLA_F64) == 0 and L.solve_workspace_bytes(8, 9) == 0
+    assert L.dla_gemm(4, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3  # A is k x m: lda >= m
+    bad = B.GemmParams(128, 128, 16, 4, 64, 64)
+    assert L.dla_gemm(4, fake, 8, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, ctypes.byref(bad), None) == B.DLA_ERR_UNSUPPORTED_PARAMS
     assert L.dla_gemm(7, fake, 8, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -1
     assert L.dla_gemm(0, None, 8, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -2
     assert L.dla_gemm(0, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3
