@@ -27,7 +27,7 @@ METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
 # HBM bytes per launch of the bulk update kernel (fetch + write), from the two rocprofv3 --pmc passes
 # summarised in profiles/update_kernel_hbm_traffic_n4000.txt (counter readings scaled by the same
 # counters' readings for a device copy of known size).  None until measured.
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74540 * 1024
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74550 * 1024
 
 
 def update_algorithmic_bytes(n, nb=128, lower=False):
@@ -73,6 +73,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n", type=int, default=N_FACTOR, help="factorisation size (default: the metric's N=4000)")
+    ap.add_argument("--lookahead", type=int, default=None,
+                    help="override the factorisations' look-ahead mode; 2 (pipeline ordered by stream events only) "
+                         "is the one to use under a profiler that serialises kernels (rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on ONE GPU; --gpus above 1 is not supported "
@@ -108,6 +111,8 @@ def main() -> int:
     p_lu = B.default_params(B.DLA_KERNEL_LU, n)
     p_ch = B.default_params(B.DLA_KERNEL_CHOLESKY, n)
     p_mm = B.default_params(B.DLA_KERNEL_MM3, dims["nk"])
+    if args.lookahead is not None:
+        p_lu.lookahead = p_ch.lookahead = args.lookahead
     ws_f = torch.empty(B.factor_workspace_bytes(n, B.DLA_F64, p_lu), dtype=torch.uint8, device=dev)
     ws_m = torch.empty(B.mm3_workspace_bytes(dims["ni"], dims["nj"], dims["nl"], B.DLA_F64), dtype=torch.uint8,
                        device=dev)

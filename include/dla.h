@@ -81,8 +81,11 @@ typedef struct {
 typedef struct {
   int nb;        /* block size, multiple of 16, 16..128 (0 = default)                          */
   int lookahead; /* 0: one stream, strictly sequential steps; 1: the next diagonal block is factored
-                    while panel solves and trailing update of this step run on helper streams;
-                    -1 = default                                                               */
+                    while panel solves and trailing update of this step run on helper streams, and
+                    the kernels of that chain wait for each other inside the kernels (needs kernels
+                    of the process to run side by side); 2: the same pipeline ordered by stream
+                    events only, for tools that serialise kernels (hardware-counter profiling,
+                    debuggers); -1 = default (1)                                                */
   dla_gemm_params update;
 } dla_factor_params;
 
@@ -102,7 +105,10 @@ typedef struct {
  *              factor_workspace_bytes(n, dt, p) bytes, 256-byte aligned.
  *   d_info     device int, may be NULL.  Written asynchronously: 0, or the
  *              1-based index of the first exactly-zero pivot, after which the
- *              content of A is unspecified (the call itself still completes).
+ *              content of A is unspecified (the call itself still completes);
+ *              or -1: with lookahead = 1 a kernel gave up waiting for its
+ *              predecessor (about 0.1 s: kernels of the process do not run side
+ *              by side), the content of A is invalid, use lookahead = 2 or 0.
  * n == 0 is a successful no-op.
  */
 int lu_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_params* p,

@@ -53,20 +53,28 @@ __device__ inline void lds_barrier() {
 
 // Hand-over between two kernels that run side by side on different streams: the producer's
 // threads make their stores visible device-wide and one of them bumps a counter; the consumer polls
-// the counter with one thread before it touches the data.  The consumer is launched early only to hide its
-// launch latency; the streams are arranged so that the producer never depends on the consumer, and
-// the poll is bounded: a consumer that gives up computes on stale data instead of hanging the GPU.
+// the counter with one thread before it touches the data.  The consumer is launched early only to
+// hide its launch latency; the streams are arranged so that the producer never depends on the
+// consumer.  The poll is bounded (about a tenth of a second), so that every wave exits even where
+// kernels of one process cannot run side by side (a profiler or debugger that serialises them):
+// the consumer that gives up sets *broken, every later wait returns at once, and the pipeline's
+// last kernel reports it.  Data computed after that is not valid.
 __device__ inline void chain_signal(int* counter, int add, int tid) {
   __threadfence();   // this thread's global stores, device scope
   __syncthreads();   // every thread of the workgroup has fenced
   if (tid == 0) __hip_atomic_fetch_add(counter, add, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ inline void chain_wait(const int* counter, int target, int tid) {
+__device__ inline void chain_wait(const int* counter, int target, int* broken, int tid) {
   if (tid == 0) {
-    for (int spins = 0; spins < (1 << 21); ++spins) {
-      if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
-      __builtin_amdgcn_s_sleep(16);
+    bool ok = false;
+    for (int spins = 0; spins < (1 << 16) && !ok; ++spins) {
+      ok = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
+      if (!ok) {
+        if ((spins & 63) == 63 && __hip_atomic_load(broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
     }
+    if (!ok) __hip_atomic_store(broken, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   __threadfence();   // acquire: loads below see what the producer published

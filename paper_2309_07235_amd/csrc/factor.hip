@@ -33,7 +33,7 @@ int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, 
   if (b == 0) b = 128;
   if (b < 16 || b > kNbMax || b % 16 != 0) return DLA_ERR_UNSUPPORTED_PARAMS;
   int la = in ? in->lookahead : -1;
-  if (la < -1 || la > 1) return DLA_ERR_UNSUPPORTED_PARAMS;
+  if (la < -1 || la > 2) return DLA_ERR_UNSUPPORTED_PARAMS;
   if (la == -1) la = 1;
   *nb = b;
   *lookahead = la;
@@ -200,7 +200,8 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     return reinterpret_cast<T*>(wsb + 4 * set + (size_t)(2 * (step & 1) + 1) * head_copy_bytes(dt));
   };
 
-  // hand-over counters of the look-ahead chain: [0] diagonal blocks factored, [1] head workgroups finished
+  // hand-over counters of the look-ahead chain: [0] diagonal blocks factored, [1] head workgroups
+  // finished, [2] set when a wait gave up
   int* const chain = reinterpret_cast<int*>(wsb + 4 * set + 4 * head_copy_bytes(dt));
   bool chained = false;  // set by the look-ahead path
   int heads_done = 0;    // head workgroups launched so far = what the next diagonal block waits for
@@ -216,6 +217,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     da.wait_counter = chained ? chain + 1 : nullptr;  // head workgroups finished so far
     da.wait_target = heads_done;
     da.done_counter = chained ? chain : nullptr;
+    da.broken = chained ? chain + 2 : nullptr;
     return launch_diag<T, KIND>(da, s, done);
   };
   // panel solves of the block column / block row behind diagonal block k0
@@ -309,7 +311,9 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     // stream, and each of its kernels is launched while its predecessor still runs: it waits for it
     // on a counter in the workspace instead of a stream dependency, which hides its launch latency.
     // Every kernel is submitted after everything it waits for, so the order of submission is a valid
-    // order of execution whatever hardware queues the streams share.
+    // order of execution whatever hardware queues the streams share.  It does need kernels of this
+    // process to run side by side; where they cannot (a profiler collecting hardware counters
+    // serialises them), lookahead = 2 keeps the same streams and orders the chain with events.
     //
     // Only the chain is handed over this way: a waiting kernel holds its compute units, and the
     // bulk update needs every unit outside the reserve at once, so a head update that also waited
@@ -394,6 +398,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       T* const Akk = A + k0 * lda + k0;
       const int64_t bn = m < nb ? m : nb;
       if (step > 0 && hipStreamWaitEvent(ctx.head, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
+      if (!chained && hipStreamWaitEvent(ctx.head, e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
       HeadArgs<T> ha;
       ha.D = Akk;
       ha.top = step == 0 ? Akk + b : head_top_of(step);
@@ -405,22 +410,24 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       ha.bn = (int)bn;
       ha.inv_lo = inv_lo_of(step);
       ha.inv_up = inv_up_of(step);
-      ha.wait_counter = chain;  // diagonal blocks factored: block k is number k + 1
+      ha.wait_counter = chained ? chain : nullptr;  // diagonal blocks factored: block k is number k + 1
       ha.wait_target = step + 1;
-      ha.done_counter = chain + 1;
+      ha.done_counter = chained ? chain + 1 : nullptr;
+      ha.broken = chain + 2;
       int head_wgs = 0, r;
       if ((r = launch_head<T, KIND>(ha, ctx.head, e_head, &head_wgs)) != DLA_SUCCESS) return r;
       heads_done += head_wgs;
+      if (!chained && hipStreamWaitEvent(st, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
       if ((r = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return r;
       return DLA_SUCCESS;
     };
 
-    chained = true;
-    hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, chain, 2);
+    chained = lookahead == 1;
+    hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, chain, 3);
     if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
     if (hipEventRecord(e_start, st) != hipSuccess || hipStreamWaitEvent(ctx.head, e_start, 0) != hipSuccess)
       return DLA_ERR_HIP;
-    if ((rc = diag(0, 0, st, nullptr)) != DLA_SUCCESS) return rc;
+    if ((rc = diag(0, 0, st, chained ? nullptr : e_diag[0])) != DLA_SUCCESS) return rc;
 
     for (int step = 0; step < nsteps; ++step) {
       if ((rc = chain_side(step)) != DLA_SUCCESS) return rc;

@@ -257,6 +257,7 @@ struct DiagArgs {
   const int* wait_counter;
   int wait_target;
   int* done_counter;
+  int* broken;   // set by a wait that gave up (see chain_wait); reported as info = -1
 };
 
 template <typename T, int KIND>
@@ -274,7 +275,7 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
   const int bp = nblk * kIb;  // padded size: rows/columns b..bp-1 are identity
 
   DLA_TRACE(0);
-  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, tid);
+  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, tid);
   if (tid == 0) s_info = 0;
   // ---- load, padding with the identity: thread = two adjacent columns, 8 rows per pass, all
   // loads issued before the first LDS store
@@ -487,6 +488,7 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
   if (tid == 0 && g.info) {
     if (g.k0 == 0) *g.info = s_info;  // first block of the call: initialise
     else if (s_info != 0 && *g.info == 0) *g.info = s_info;
+    if (g.broken && __hip_atomic_load(g.broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) *g.info = -1;
   }
   if (g.done_counter) chain_signal(g.done_counter, 1, tid);
 }

@@ -46,9 +46,11 @@ struct HeadArgs {
   const T* inv_up;  // inverted diagonal sub-blocks of the upper factor (LU)
   // D and the inverses are ready once *wait_counter >= wait_target (diagonal blocks factored so far);
   // every workgroup increments *done_counter when its tile is stored
+  // (both null when the streams order the two kernels instead)
   const int* wait_counter;
   int wait_target;
   int* done_counter;
+  int* broken;      // set by a wait that gave up (see chain_wait)
 };
 
 template <typename T, int KIND>
@@ -169,7 +171,7 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
 
   // The panel heads and the tile (requested above) do not depend on the diagonal block of this step,
   // the factors below do: the kernel is launched while that block is still being factored.
-  chain_wait(g.wait_counter, g.wait_target, tid);
+  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, tid);
 
   // ---- stage the factors: one element per thread and sub-block, all loads before the first LDS store
   {
@@ -236,7 +238,7 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
     if (r < rows_valid && l15 < cols_valid) Ct[(int64_t)r * lda + l15] = c[v];
   }
   }
-  chain_signal(g.done_counter, 1, tid);
+  if (g.done_counter) chain_signal(g.done_counter, 1, tid);
 }
 
 // --------------------------------------------------------------------------------------

@@ -100,6 +100,8 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.lu_factor(vp(0x1004), 8, 8, B.DLA_F64, None, fake, 1 << 20, None, None) == -1  # misaligned
     bad = B.FactorParams(100, 0, B.GemmParams(0, 0, 0, 0, 0, 0))
     assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    bad = B.FactorParams(64, 3, B.GemmParams(0, 0, 0, 0, 0, 0))  # look-ahead modes are 0, 1, 2
+    assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
     bad = B.FactorParams(64, 0, B.GemmParams(48, 48, 0, 0, 0, 0))
     assert L.cholesky_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
     assert L.lu_factor(fake, 512, 512, B.DLA_F64, None, None, 0, None, None) == B.DLA_ERR_WORKSPACE

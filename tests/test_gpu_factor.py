@@ -152,7 +152,7 @@ def test_lu_n2000_nb128(B, oracle):
     _check_lu(oracle, got, A, 2000)
 
 
-@pytest.mark.parametrize("lookahead", [0, 1])
+@pytest.mark.parametrize("lookahead", [0, 1, 2])
 def test_n4000_both(B, oracle, lookahead):
     """The size the headline metric is quoted on, in the launch configuration the benchmark uses."""
     announce(f"lu + cholesky N=4000 lookahead={lookahead}")
