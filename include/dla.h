@@ -237,6 +237,16 @@ int dla_profile_read(int phase, double* ms_total, int64_t* launches, double* flo
 int dla_mfma_peak(dla_dtype dt, void* d_scratch, size_t scratch_bytes, void* hip_stream, double* tflops);
 size_t dla_mfma_peak_scratch_bytes(void);
 
+/*
+ * Diagnostic for the look-ahead pipeline's in-kernel waits (dla_factor_params.lookahead = 1): runs one
+ * diagonal-block kernel that is told to wait for a predecessor that does not exist.  After the bounded
+ * poll (about 0.1 s) it gives up and reports *d_info = -1, which is what a factorisation reports where
+ * kernels cannot run side by side; the kernel exits normally.  d_scratch: device, 256-byte aligned,
+ * at least 8192 bytes, overwritten.  d_info: device int, must be preset by the caller (it is only
+ * written on the report).
+ */
+int dla_handover_selftest(void* d_scratch, size_t scratch_bytes, void* hip_stream, int* d_info);
+
 const char* dla_strerror(int code);
 const char* dla_version(void);
 

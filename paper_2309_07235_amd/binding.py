@@ -80,6 +80,8 @@ def _load() -> ctypes.CDLL:
     lib.dla_mfma_peak.restype = ci
     lib.dla_mfma_peak_scratch_bytes.argtypes = []
     lib.dla_mfma_peak_scratch_bytes.restype = ctypes.c_size_t
+    lib.dla_handover_selftest.argtypes = [vp, sz, vp, vp]
+    lib.dla_handover_selftest.restype = ci
     lib.dla_rank_update.argtypes = [ci, vp, vp, vp, i64, i64, i64, ci, vp]
     lib.dla_rank_update.restype = ci
     lib.dla_gemm_params_supported.argtypes = [ci, ctypes.POINTER(GemmParams)]
@@ -277,6 +279,16 @@ def dla_rank_update(lower: bool, l, r, c, stream=None):
         raise ValueError("dla_rank_update: l, r and c must share one leading dimension")
     _check(lib.dla_rank_update(1 if lower else 0, lp, rp, cp, ldl, m, k, dt, ctypes.c_void_p(_stream_ptr(stream))),
            "dla_rank_update")
+
+
+def handover_selftest(stream=None) -> int:
+    """Runs the look-ahead pipeline's wait with nothing to wait for; returns what it reported (-1 expected)."""
+    import torch
+    scratch = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    _check(lib.dla_handover_selftest(ctypes.c_void_p(scratch.data_ptr()), 8192, ctypes.c_void_p(_stream_ptr(stream)),
+                                     ctypes.c_void_p(info.data_ptr())), "dla_handover_selftest")
+    return int(info.item())
 
 
 def mfma_peak(dt: int = DLA_F64, stream=None) -> float:

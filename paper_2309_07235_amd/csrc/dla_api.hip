@@ -502,6 +502,13 @@ int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t n
   return solve_impl<float, 1>((const float*)d_l, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
 }
 
+int dla_handover_selftest(void* d_scratch, size_t scratch_bytes, void* hip_stream, int* d_info) {
+  if (!d_scratch || ((uintptr_t)d_scratch % 256)) return -1;
+  if (scratch_bytes < kHandoverSelftestBytes) return -2;
+  if (!d_info) return -4;
+  return handover_selftest_impl(d_scratch, static_cast<hipStream_t>(hip_stream), d_info);
+}
+
 int dla_profile_enable(int on) {
   std::lock_guard<std::mutex> lock(g_profile_mutex);
   g_profile_on = (on != 0);

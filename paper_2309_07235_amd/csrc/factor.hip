@@ -454,6 +454,30 @@ int rank_update_impl(bool lower, const T* L, const T* Rm, T* C, int64_t ld, int6
 template int rank_update_impl<double>(bool, const double*, const double*, double*, int64_t, int64_t, int, hipStream_t);
 template int rank_update_impl<float>(bool, const float*, const float*, float*, int64_t, int64_t, int, hipStream_t);
 
+// Diagnostic: one diagonal-block kernel told to wait for a predecessor that does not exist.  It
+// must give up after the bounded poll, mark the pipeline broken and report -1, and exit normally.
+// scratch: >= kHandoverSelftestBytes, 256-byte aligned: a 16 x 16 identity, its inverses, counters.
+int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info) {
+  double* const A = static_cast<double*>(scratch);  // 16 x 16
+  double* const inv = A + 256;                      // 2 x 256
+  int* const chain = reinterpret_cast<int*>(inv + 512);
+  hipLaunchKernelGGL(identity16_kernel, dim3(1), dim3(256), 0, st, A, chain);
+  if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+  DiagArgs<double> da;
+  da.A = A;
+  da.lda = 16;
+  da.b = 16;
+  da.k0 = 16;  // not the first block of a call: info is only touched to report
+  da.info = d_info;
+  da.inv_lo = inv;
+  da.inv_up = inv + 256;
+  da.wait_counter = chain + 1;
+  da.wait_target = 1;  // nobody will ever count to one
+  da.done_counter = chain;
+  da.broken = chain + 2;
+  return launch_diag<double, KIND_LU>(da, st, nullptr);
+}
+
 template <typename T>
 int lu_factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
                    hipStream_t st, int* d_info) {

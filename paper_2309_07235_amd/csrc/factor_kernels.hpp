@@ -503,6 +503,13 @@ static __global__ void zero_ints_kernel(int* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 
+// A 16 x 16 identity and three zeroed counters (the hand-over self-test's input).
+static __global__ void identity16_kernel(double* a, int* counters) {
+  const int t = (int)threadIdx.x;
+  a[t] = (t / 16 == t % 16) ? 1.0 : 0.0;
+  if (t < 3) counters[t] = 0;
+}
+
 // Zero the strict upper triangle (Cholesky output convention).
 template <typename T>
 __global__ void __launch_bounds__(256) zero_upper_kernel(T* A, int64_t lda, int n) {

@@ -75,6 +75,8 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
                hipStream_t st);
 size_t solve_workspace_bytes_impl(int64_t n, dla_dtype dt);
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p);
+constexpr size_t kHandoverSelftestBytes = 8192;
+int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info);
 int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
                           GemmSchedule* upd);
 

@@ -159,6 +159,9 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.dla_gemm(0, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3
     assert L.dla_gemm(2, fake, 8, fake, 8, fake, 8, 8, 6, 8, B.DLA_F64, None, None) == -9
     assert L.dla_gemm(0, fake, 8, fake, 8, fake, 8, 0, 8, 8, B.DLA_F64, None, None) == 0
+    assert L.dla_handover_selftest(None, 8192, None, fake) == -1
+    assert L.dla_handover_selftest(fake, 100, None, fake) == -2
+    assert L.dla_handover_selftest(fake, 8192, None, None) == -4
     assert L.dla_rank_update(2, fake, fake, fake, 256, 64, 16, B.DLA_F64, None) == -1
     assert L.dla_rank_update(0, None, fake, fake, 256, 64, 16, B.DLA_F64, None) == -2
     assert L.dla_rank_update(0, fake, None, fake, 256, 64, 16, B.DLA_F64, None) == -3

@@ -407,3 +407,18 @@ def test_back_to_back_calls_share_the_helper_streams(B, oracle):
             _check_lu(oracle, to_host(d), H, n)
         else:
             _check_chol(oracle, to_host(d), H, n)
+
+
+def test_a_wait_that_cannot_end_gives_up_and_is_reported(B, oracle):
+    """The pipeline's in-kernel wait is bounded: with nothing to wait for, the kernel ends after the poll and
+    reports -1 (forced from the host: the counter it polls is never touched; every wave exits normally).
+    A normal factorisation right after it is unaffected."""
+    import time
+    announce("hand-over self-test")
+    t0 = time.perf_counter()
+    assert B.handover_selftest() == -1
+    assert time.perf_counter() - t0 < 5.0
+    A = inputs.diag_dominant_matrix(700, 41)
+    got, info = _gpu_lu(B, A)
+    assert info == 0
+    _check_lu(oracle, got, A, 700)
