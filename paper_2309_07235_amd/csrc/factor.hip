@@ -10,6 +10,7 @@ namespace dla {
 
 constexpr int kNumCu = 256;   // compute units of an MI355X
 constexpr int kChainCu = 32;  // left to the latency chain while a bulk update runs
+constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot gets at least this many
 
 static inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -64,13 +65,13 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = n
 }
 
 // Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp).
-template <typename T, int KIND>
-static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
-                         hipStream_t st, hipEvent_t done = nullptr) {
-  if (m <= 0) return DLA_SUCCESS;
+template <typename T, int KIND, int NCB>
+static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
+                             hipStream_t st, hipEvent_t done) {
   constexpr bool LOWER = (KIND == KIND_CHOL);
-  auto kern = update_kernel<T, LOWER>;
-  using LD = UpdateLds<T, LOWER>;
+  constexpr int COLS = NCB * 16;
+  auto kern = update_kernel<T, LOWER, NCB>;
+  using LD = UpdateLds<T, LOWER, NCB>;
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -88,14 +89,14 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
   a.skip = skip;
   const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
   int64_t total_blocks = 0;
-  for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)m, LOWER);
+  for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)m, LOWER, COLS);
   // one 8-wave workgroup fits per compute unit: aim at one round of at most `slots` items
   a.bpi = (int)((total_blocks + slots - 1) / slots);
   if (a.bpi < 1) a.bpi = 1;
   int items = 0;
   for (;;) {
     items = 0;
-    for (int p = 0; p < npanels; ++p) items += update_items_of_panel(p, (int)m, a.bpi, LOWER);
+    for (int p = 0; p < npanels; ++p) items += update_items_of_panel(p, (int)m, a.bpi, LOWER, COLS);
     if (items <= slots || a.bpi >= (1 << 20)) break;
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
@@ -104,6 +105,23 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
   ProfileScope scope(PHASE_UPDATE, flops, st);
   launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+}
+
+// fp32: 64-column blocks once every slot gets at least kWideMinBlocks of them (3-6 % faster at
+// N = 8192), 32-column blocks below.  fp64 always takes 32-column blocks: three accumulator sets of
+// a 64-column block do not fit the register file next to the left panel (it spills and halves the rate).
+template <typename T, int KIND>
+static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
+                         hipStream_t st, hipEvent_t done = nullptr) {
+  if (m <= 0) return DLA_SUCCESS;
+  const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
+  int64_t wide_blocks = 0;
+  for (int p = 0; p < npanels; ++p) wide_blocks += update_blocks_of_panel(p, (int)m, KIND == KIND_CHOL, 64);
+  if constexpr (sizeof(T) == 4) {  // the wide form does not fit the register file in fp64
+    if (wide_blocks >= (int64_t)kWideMinBlocks * slots)
+      return launch_update_ncb<T, KIND, 4>(L, R, C, ld, m, b, skip, slots, st, done);
+  }
+  return launch_update_ncb<T, KIND, 2>(L, R, C, ld, m, b, skip, slots, st, done);
 }
 
 template <typename T, int KIND>

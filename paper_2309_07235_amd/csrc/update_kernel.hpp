@@ -8,10 +8,13 @@
 //
 //   - a workgroup (8 waves) owns 128 rows of L21; every wave keeps its 16 x b slice as MFMA
 //     left-operand fragments IN REGISTERS (negated, so the accumulators can start from C);
-//   - the workgroup then walks a range of 32-column blocks of the trailing matrix: the b x 32
-//     block of the right operand is staged through double-buffered LDS, the 16 x 32 block of C per
-//     wave is prefetched into registers one iteration ahead, 64 MFMAs per wave and iteration
-//     run from registers + LDS, and the finished block is stored while the next one computes.
+//   - the workgroup then walks a range of column blocks of the trailing matrix, 32 or 64 columns
+//     wide (NCB = 2 or 4 MFMA blocks; the wide form for large trailing matrices, whose rows are
+//     then touched in 512-byte pieces, the narrow one where the wide one would leave compute units
+//     without work): the b x cols block of the right operand is staged through double-buffered
+//     LDS, the 16 x cols block of C per wave is prefetched into registers two iterations ahead,
+//     32 * NCB MFMAs per wave and iteration run from registers + LDS, and the finished block is
+//     stored while the next one computes.
 //   - the eight waves form two groups of four (one wave of each group per SIMD) that take turns
 //     on the MFMA pipes: while one group multiplies a column block, the other stores its previous
 //     result, fetches its share of the next right-operand block and its next C block, and writes
@@ -30,7 +33,6 @@
 namespace dla {
 
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
-constexpr int kUpdCols = 32;    // columns per iteration
 constexpr int kUpdThreads = 512;
 constexpr int kUpdKMax = 128;   // largest block size b
 
@@ -41,17 +43,17 @@ struct UpdateArgs {
   T* C;         // m x m trailing matrix
   int64_t ld;   // common leading dimension (all three live in the same matrix)
   int m, b;
-  int bpi;      // target number of 32-column blocks per work item
+  int bpi;      // target number of column blocks per work item
   int items;    // number of work items = grid size
   int skip;     // the leading skip x skip block of C (skip: multiple of 16) is not written: another stream owns it
 };
 
-template <typename T, bool LOWER>
+template <typename T, bool LOWER, int NCB>
 struct UpdateLds {
-  // The b x 32 right-operand block is stored in MFMA fragment order: element (k, col) sits at
-  // ((k/4)*2 + col/16)*64 + (k%4)*16 + col%16, i.e. the 64 values one wave reads for k-step k/4 and
+  // The b x cols right-operand block is stored in MFMA fragment order: element (k, col) sits at
+  // ((k/4)*NCB + col/16)*64 + (k%4)*16 + col%16, i.e. the 64 values one wave reads for k-step k/4 and
   // column block col/16 are contiguous in lane order, so fragment reads are conflict free.
-  static constexpr int B_ELEMS = kUpdKMax * kUpdCols;
+  static constexpr int B_ELEMS = kUpdKMax * NCB * 16;
   static constexpr int B_PAD = B_ELEMS;
   // the left panel is staged through the same memory, 64 k-columns at a time: [rows][65]
   static constexpr int A_HALF = kUpdRows * 65;
@@ -59,19 +61,20 @@ struct UpdateLds {
   static constexpr int BYTES = ELEMS * (int)sizeof(T);
 };
 
-// 32-column blocks row panel p (0-based) has to update, and the number of work items it is cut into
-__host__ __device__ inline int update_blocks_of_panel(int p, int m, bool lower) {
+// column blocks (cols wide) row panel p (0-based) has to update, and the number of work items it is cut into
+__host__ __device__ inline int update_blocks_of_panel(int p, int m, bool lower, int cols) {
   const int width = lower ? ((p + 1) * kUpdRows < m ? (p + 1) * kUpdRows : m) : m;
-  return (width + kUpdCols - 1) / kUpdCols;
+  return (width + cols - 1) / cols;
 }
-__host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool lower) {
-  return (update_blocks_of_panel(p, m, lower) + bpi - 1) / bpi;
+__host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool lower, int cols) {
+  return (update_blocks_of_panel(p, m, lower, cols) + bpi - 1) / bpi;
 }
 
-template <typename T, bool LOWER>
+template <typename T, bool LOWER, int NCB>
 __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
   using acc_t = typename Mfma<T>::acc_t;
-  using LD = UpdateLds<T, LOWER>;
+  using LD = UpdateLds<T, LOWER, NCB>;
+  constexpr int kUpdCols = NCB * 16;  // columns per iteration
   constexpr int KSTEPS = kUpdKMax / 4;  // 32
   extern __shared__ __align__(16) unsigned char smem_raw[];
   T* const smem = reinterpret_cast<T*>(smem_raw);
@@ -86,7 +89,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   int item = xcd_contiguous_id((int)blockIdx.x, g.items);
   int panel = 0, cnt = 0;
   for (;;) {
-    cnt = update_items_of_panel(panel, m, g.bpi, LOWER);
+    cnt = update_items_of_panel(panel, m, g.bpi, LOWER, kUpdCols);
     if (item < cnt || panel + 1 >= npanels) break;
     item -= cnt;
     ++panel;
@@ -96,7 +99,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   // q + 2*cnt, ...  Items run side by side, so at any moment the items of one panel touch a run of
   // adjacent 256-byte pieces of the same matrix rows (DRAM page locality), and every panel is at
   // about the same right-operand block (L2 reuse).
-  const int nblocks = update_blocks_of_panel(panel, m, LOWER);
+  const int nblocks = update_blocks_of_panel(panel, m, LOWER, kUpdCols);
   const int width = LOWER ? ((panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m) : m;
   const int col_begin = item * kUpdCols;         // first block of this item
   const int col_step = cnt * kUpdCols;           // distance between its blocks
@@ -141,9 +144,9 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   }
 
   // ---- right-operand block loader: b x 32 block starting at column j0 -> registers -> LDS ------
-  // LU:       rows k of U12, 32 contiguous columns: thread -> (k = tid / 4, 8 columns)
-  // Cholesky: rows j0..j0+31 of L21, b contiguous k: thread -> (row = tid % 32, 8 k-values at (tid / 32) * 8)
-  constexpr int BPT = kUpdKMax * kUpdCols / kUpdThreads;  // 8 elements per thread
+  // LU:       rows k of U12, cols contiguous columns: thread -> (k = tid / 4, cols / 4 columns)
+  // Cholesky: rows j0..j0+cols-1 of L21, b contiguous k: thread -> (row = tid % cols, BPT k-values)
+  constexpr int BPT = kUpdKMax * kUpdCols / kUpdThreads;  // 8 or 16 elements per thread
   T bst[BPT];
   auto fetch_b = [&](int j0) {
     if (!LOWER) {
@@ -162,7 +165,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
         }
       }
     } else {
-      const int r = tid & 31, k0 = (tid >> 5) * BPT;
+      const int r = tid % kUpdCols, k0 = (tid / kUpdCols) * BPT;
       const int gr = (j0 + r < m) ? j0 + r : m - 1;
       const T* p = g.R + (int64_t)gr * ld;
       const bool full = (j0 + r < m) && (k0 + BPT <= b);
@@ -182,36 +185,35 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   auto stash_b = [&](int buf) {
     T* sb = smem + buf * LD::B_PAD;
     if (!LOWER) {
-      const int k = tid >> 2, c0 = (tid & 3) * BPT;  // 8 consecutive columns inside one 16-column block
-      T* d = sb + ((k >> 2) * 2 + (c0 >> 4)) * 64 + (k & 3) * 16 + (c0 & 15);
+      const int k = tid >> 2, c0 = (tid & 3) * BPT;  // BPT consecutive columns inside one 16-column block
+      T* d = sb + ((k >> 2) * NCB + (c0 >> 4)) * 64 + (k & 3) * 16 + (c0 & 15);
 #pragma unroll
       for (int i = 0; i < BPT; ++i) d[i] = bst[i];
     } else {
-      const int col = tid & 31, k0 = (tid >> 5) * BPT;  // 8 consecutive k of one column
+      const int col = tid % kUpdCols, k0 = (tid / kUpdCols) * BPT;  // BPT consecutive k of one column
 #pragma unroll
       for (int i = 0; i < BPT; ++i) {
         const int k = k0 + i;
-        sb[((k >> 2) * 2 + (col >> 4)) * 64 + (k & 3) * 16 + (col & 15)] = bst[i];
+        sb[((k >> 2) * NCB + (col >> 4)) * 64 + (k & 3) * 16 + (col & 15)] = bst[i];
       }
     }
   };
-  // ---- C block of this wave: 16 rows x 32 columns = 2 MFMA blocks ---------------------------------
+  // ---- C block of this wave: 16 rows x cols columns = NCB MFMA blocks ------------------------------
   T* const Cw = g.C + (int64_t)wrow0 * ld;
-  auto fetch_c = [&](acc_t (&c)[2], int j0) {
+  auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
 #ifdef DLA_UPD_NO_CLOAD  // development switch: measure the kernel without its C reads
-    c[0] = acc_t{0, 0, 0, 0};
-    c[1] = acc_t{0, 0, 0, 0};
+    for (int q = 0; q < NCB; ++q) c[q] = acc_t{0, 0, 0, 0};
     return;
 #endif
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
     if (full) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+      for (int q = 0; q < NCB; ++q)
 #pragma unroll
         for (int v = 0; v < 4; ++v) c[q][v] = Cw[(int64_t)Mfma<T>::row_of(v, lane) * ld + j0 + q * 16 + l15];
     } else {
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+      for (int q = 0; q < NCB; ++q)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
@@ -221,13 +223,13 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
         }
     }
   };
-  auto store_c = [&](const acc_t (&c)[2], int j0) {
+  auto store_c = [&](const acc_t (&c)[NCB], int j0) {
 #ifdef DLA_UPD_NO_STORE  // development switch: keep one store per wave so the work is not optimised away
     if (j0 != col_begin) return;
 #endif
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < NCB; ++q) {
       if (wrow0 < g.skip && j0 + q * 16 < g.skip) continue;  // uniform per wave: the excluded leading block
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
@@ -236,20 +238,20 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
       }
     }
   };
-  auto multiply = [&](acc_t (&c)[2], int buf) {
+  auto multiply = [&](acc_t (&c)[NCB], int buf) {
     const T* sb = smem + buf * LD::B_PAD + lane;
-    T f0 = sb[0], f1 = sb[64];
+    T f[NCB], nx[NCB];
+#pragma unroll
+    for (int q = 0; q < NCB; ++q) f[q] = sb[q * 64];
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
-      T n0 = T(0), n1 = T(0);
-      if (kk + 1 < KSTEPS) {  // fragments of the next k-step are requested before this step's MFMAs issue
-        n0 = sb[(kk + 1) * 128];
-        n1 = sb[(kk + 1) * 128 + 64];
-      }
-      c[0] = Mfma<T>::mma(afrag[kk], f0, c[0]);
-      c[1] = Mfma<T>::mma(afrag[kk], f1, c[1]);
-      f0 = n0;
-      f1 = n1;
+#pragma unroll
+      for (int q = 0; q < NCB; ++q)  // fragments of the next k-step are requested before this step's MFMAs issue
+        nx[q] = (kk + 1 < KSTEPS) ? sb[((kk + 1) * NCB + q) * 64] : T(0);
+#pragma unroll
+      for (int q = 0; q < NCB; ++q) c[q] = Mfma<T>::mma(afrag[kk], f[q], c[q]);
+#pragma unroll
+      for (int q = 0; q < NCB; ++q) f[q] = nx[q];
     }
   };
   // ---- pipeline over the column blocks, the two wave groups in anti-phase -------------------------
@@ -262,7 +264,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   // Prefetch distances: the right-operand share in bst is fetched one whole block step before it is
   // written to LDS, and a C block is fetched two steps before it is multiplied (three accumulator
   // sets rotate), so neither the LDS write nor the first MFMA of a step waits on a fresh load.
-  auto side_work = [&](acc_t (&done)[2], int jdone, bool have_done, acc_t (&tgt)[2], int jc, int buf) {
+  auto side_work = [&](acc_t (&done)[NCB], int jdone, bool have_done, acc_t (&tgt)[NCB], int jc, int buf) {
     const int jn = jc + col_step, jnn = jc + 2 * col_step;
     if (jn < col_end) stash_b(buf ^ 1);  // block jn, fetched during the previous step
     if (jnn < col_end) fetch_b(jnn);     // block after that
@@ -270,7 +272,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
     if (jnn < col_end) fetch_c(tgt, jnn);
   };
   DLA_TRACE(1);
-  acc_t c0[2], c1[2], c2[2];
+  acc_t c0[NCB], c1[NCB], c2[NCB];
   fetch_b(col_begin);
   fetch_c(c0, col_begin);
   stash_b(0);
@@ -284,7 +286,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   // One block step.  cur holds this block's C; tgt is the set that becomes free in this step and
   // receives the C block two steps ahead.  Group 0 frees cur's predecessor itself (it stores right
   // after multiplying); for group 1 the previous block's result still sits in tgt when the step begins.
-  auto block_step = [&](acc_t (&cur)[2], acc_t (&tgt)[2], int jp, int jc, bool first, int b_) {
+  auto block_step = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp, int jc, bool first, int b_) {
     if (grp == 0) {
       DLA_TRACE(8);
       multiply(cur, b_);
