@@ -131,9 +131,10 @@ int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_f
  *                read only.
  *   d_b          device, n x nrhs, row-major with leading dimension ldb (every column is one
  *                right-hand side); overwritten by X.  Must not overlap the factor.
- *   d_workspace / workspace_bytes   device scratch of at least solve_workspace_bytes(n, dt) bytes,
- *                256-byte aligned: the diagonal blocks of the factor prepared for the two
- *                substitutions (about 1.3 KB per row of the factor in fp64).
+ *   d_workspace / workspace_bytes   device scratch of at least solve_workspace_bytes(n, nrhs, dt)
+ *                bytes, 256-byte aligned: the inverted 128 x 128 diagonal blocks of the factor
+ *                for the two substitutions (2 KB per row of the factor in fp64) and the
+ *                intermediate n x nrhs solution of the forward pass.
  * n == 0 or nrhs == 0 is a successful no-op that needs no workspace.  A zero on the factor's diagonal
  * gives infinities or NaNs in X; nothing is reported (the factorisation's d_info already said so).
  */
@@ -143,7 +144,7 @@ int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t n
                    void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Scratch bytes lu_solve / cholesky_solve need (same for both). 0 on invalid arguments. */
-size_t solve_workspace_bytes(int64_t n, dla_dtype dt);
+size_t solve_workspace_bytes(int64_t n, int64_t nrhs, dla_dtype dt);
 
 /* Scratch bytes lu_factor / cholesky_factor need (same for both). 0 on invalid arguments. */
 size_t factor_workspace_bytes(int64_t n, dla_dtype dt, const dla_factor_params* p);

@@ -62,7 +62,7 @@ def _load() -> ctypes.CDLL:
     lib.cholesky_factor.argtypes = lib.lu_factor.argtypes
     lib.cholesky_factor.restype = ci
     lib.lu_solve.argtypes = [vp, i64, i64, vp, i64, i64, ci, vp, sz, vp]
-    lib.solve_workspace_bytes.argtypes = [i64, ci]
+    lib.solve_workspace_bytes.argtypes = [i64, i64, ci]
     lib.solve_workspace_bytes.restype = sz
     lib.lu_solve.restype = ci
     lib.cholesky_solve.argtypes = lib.lu_solve.argtypes
@@ -210,8 +210,8 @@ def cholesky_factor(a, p: FactorParams | None = None, workspace=None, info=None,
     return _factor(lib.cholesky_factor, "cholesky_factor", a, p, workspace, info, stream)
 
 
-def solve_workspace_bytes(n: int, dt: int) -> int:
-    return int(lib.solve_workspace_bytes(n, dt))
+def solve_workspace_bytes(n: int, nrhs: int, dt: int) -> int:
+    return int(lib.solve_workspace_bytes(n, nrhs, dt))
 
 
 def _solve(fn, name: str, f, b, workspace, stream):
@@ -224,7 +224,7 @@ def _solve(fn, name: str, f, b, workspace, stream):
     if _dtype_code(b) != dt:
         raise ValueError(f"{name}: factor and right-hand sides differ in dtype")
     (fp, ldf), (bp, ldb) = _matrix(f, "factor"), _matrix(b, "b")
-    ws, wsp, wsb = _workspace(solve_workspace_bytes(n, dt), f.device, workspace)
+    ws, wsp, wsb = _workspace(solve_workspace_bytes(n, b.shape[1], dt), f.device, workspace)
     _check(fn(fp, n, ldf, bp, b.shape[1], ldb, dt, wsp, wsb, ctypes.c_void_p(_stream_ptr(stream))), name)
     return ws
 

@@ -477,9 +477,9 @@ static int solve_common_checks(const void* d_f, int64_t n, int64_t lda, void* d_
   return DLA_SUCCESS;
 }
 
-size_t solve_workspace_bytes(int64_t n, dla_dtype dt) {
-  if (n < 0 || n > kMaxDim || (dt != DLA_F64 && dt != DLA_F32)) return 0;
-  return solve_workspace_bytes_impl(n, dt);
+size_t solve_workspace_bytes(int64_t n, int64_t nrhs, dla_dtype dt) {
+  if (n < 0 || n > kMaxDim || nrhs < 0 || nrhs > kMaxDim || (dt != DLA_F64 && dt != DLA_F32)) return 0;
+  return solve_workspace_bytes_impl(n, nrhs, dt);
 }
 
 int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,

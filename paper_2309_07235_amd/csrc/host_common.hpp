@@ -73,7 +73,7 @@ int rank_update_impl(bool lower, const T* L, const T* Rm, T* C, int64_t ld, int6
 template <typename T, int KIND>
 int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t ldb, void* ws, size_t ws_bytes,
                hipStream_t st);
-size_t solve_workspace_bytes_impl(int64_t n, dla_dtype dt);
+size_t solve_workspace_bytes_impl(int64_t n, int64_t nrhs, dla_dtype dt);
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p);
 constexpr size_t kHandoverSelftestBytes = 8192;
 int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info);

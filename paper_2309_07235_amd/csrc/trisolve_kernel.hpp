@@ -1,24 +1,22 @@
 // Solving with the factors (paper, Section "Linear Algebra Benchmarks": both decompositions are
 // introduced as the way to solve systems of linear equations):  A X = B  becomes  L Y = B, U X = Y
 // after lu_factor and  L Y = B, L^T X = Y  after cholesky_factor.  The host driver walks the
-// triangular matrix in blocks of up to 128 rows; per block this kernel solves the block's own
-// triangular system for all right-hand sides, and a tiled GEMM carries the solved rows into the
-// rows that are still open.
+// triangular matrix in blocks of up to 128 rows.  The blocks' own triangular systems are taken off
+// the chain of the substitution by inverting every diagonal block up front (this kernel: one
+// workgroup per block, all blocks at once, independent of the right-hand sides), so that each step of
+// the chain is two small products on the tiled GEMM: X_k = W_k * B_k, then the rows still open
+// -= (factor's block column k) * X_k.
 //
-// The kernel is the panel solve of the factorisations turned by 90 degrees: a wavefront owns 16
-// right-hand sides (columns of B) as eight 16 x 16 accumulator blocks and runs the blocked
-// forward substitution of head_solve on MFMA.  All four triangular matrices are brought to the
-// one form that routine takes, lower triangular M' with  X' = M'^-1 P':
+// The inversion is the panel solve of the factorisations run on the identity: the block is brought
+// to the form head_solve takes, lower triangular M' with 16 x 16 sub-blocks whose diagonal ones are
+// inverted in registers (one 16-lane row per sub-block), and a wavefront then owns 16 columns of
+// the identity as eight accumulator blocks and substitutes on MFMA.
 //   TRI_LOWER_UNIT   M' = L (unit diagonal implied; LU forward pass)
 //   TRI_LOWER        M' = L (Cholesky forward pass)
 //   TRI_UPPER        M' = J U J    with J the reversal of the block's rows (LU backward pass)
 //   TRI_LOWER_TRANS  M' = J L^T J  (Cholesky backward pass; L^T is never formed in memory)
-// and P' = B resp. J B.  A block shorter than a multiple of 16 is padded with the identity.
-// head_solve wants the diagonal 16 x 16 sub-blocks inverted.  The inverses the factorisation made
-// are gone with its workspace, so a pre-pass (tri_prepare_kernel, one workgroup per diagonal block,
-// all blocks at once) stages every M', inverts its sub-blocks in registers, one 16-lane row per
-// sub-block, and leaves the result in the solve's workspace; trisolve_kernel, which sits on the
-// chain of the substitution, then only loads one contiguous run.
+// The result is stored un-reversed, W = J M'^-1 J.  A block shorter than a multiple of 16 is padded
+// with the identity.
 #pragma once
 #include "head_kernel.hpp"
 
@@ -26,15 +24,6 @@ namespace dla {
 
 enum TriMode { TRI_LOWER_UNIT = 0, TRI_LOWER = 1, TRI_UPPER = 2, TRI_LOWER_TRANS = 3 };
 constexpr int kTriThreads = 256;
-
-template <typename T>
-struct TriSolveArgs {
-  const T* M;   // the block as tri_prepare_kernel left it in the workspace
-  T* B;         // the block's rows of the right-hand sides (b x nrhs), overwritten by the solution
-  int64_t ldb;
-  int b;        // 1 <= b <= kNbMax
-  int nrhs;
-};
 
 template <typename T>
 constexpr int trisolve_lds_bytes() {
@@ -65,16 +54,13 @@ __device__ inline void tri_inv16(const T (&a)[16], const T (&rdiag)[16], T (&x)[
   });
 }
 
-// Pre-pass, one workgroup per diagonal block of the factor: stages M' of that block, inverts its
-// diagonal sub-blocks, and writes the result (the layout head_solve reads) to the workspace.  It
-// does not depend on the right-hand sides, so it runs once per call, all blocks in parallel,
-// instead of on the chain of the substitution.
+// One workgroup per diagonal block of the factor.
 template <typename T>
 struct TriPrepareArgs {
   const T* F;   // the factor (n x n, leading dimension lda)
   int64_t lda;
   int64_t n;
-  T* out;       // one staged block of trisolve_lds_bytes<T>() bytes per diagonal block
+  T* out;       // one 128 x 128 inverse per diagonal block
 };
 
 template <typename T, int MODE>
@@ -151,76 +137,30 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
   }
   __syncthreads();
 
-  // ---- out: the slots in use, as they sit in LDS (padding elements included: they are never read)
-  T* const out = g.out + (int64_t)blockIdx.x * (NTRI * kBlk);
-  const int used = (nblk * (nblk + 1) / 2) * kBlk;
-  for (int e = tid; e < used; e += kTriThreads) out[e] = tri[e];
-}
-
-// REV: the block's rows are taken in reverse order (the backward passes).
-template <typename T, bool REV>
-__global__ void __launch_bounds__(kTriThreads) trisolve_kernel(const TriSolveArgs<T> g) {
-  constexpr int NB = kNbMax / kIb;
+  // ---- the block's inverse: the substitution run on the identity, 16 columns per wave and pass.
+  // out holds W = M^-1 for the block in its own (un-reversed) index space, 128 x 128 row-major, so
+  // that the solve itself is the plain product W * B; what lies outside the b x b block is never read.
   using acc_t = typename Mfma<T>::acc_t;
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  T* const tri = reinterpret_cast<T*>(smem_raw);
-
-  const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l15 = lane & 15, l4 = lane >> 4;
-  const int b = g.b, nblk = (b + kIb - 1) / kIb, bp = nblk * kIb;
-  const int64_t ldb = g.ldb;
-  auto orig = [&](int i) { return REV ? bp - 1 - i : i; };  // row of the block behind row i of M'
-
-  // ---- right-hand sides into the accumulators: register v of acc[s] is row 16 s + 4 l4 + v of P'
-  const int slice0 = ((int)blockIdx.x * (kTriThreads / 64) + wave) * kIb;
-  const bool job_on = slice0 < g.nrhs;
-  const int t_valid = g.nrhs - slice0 < kIb ? g.nrhs - slice0 : kIb;
-  const int t = slice0 + (l15 < t_valid ? l15 : t_valid - 1);
-  acc_t acc[NB];
+  T* const out = g.out + (int64_t)blockIdx.x * (kNbMax * kNbMax);
+  for (int pass = 0; pass < NB / (kTriThreads / 64); ++pass) {
+    const int slice = pass * (kTriThreads / 64) + wave;
+    if (slice < nblk) {  // uniform per wave
+      acc_t acc[NB];
 #pragma unroll
-  for (int s = 0; s < NB; ++s) {
+      for (int s = 0; s < NB; ++s)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int ii = orig(s * kIb + 4 * l4 + v);
-      const bool in = job_on && s < nblk && ii < b;
-      const T x = g.B[(int64_t)(in ? ii : 0) * ldb + (job_on ? t : 0)];
-      acc[s][v] = in ? x : T(0);
-    }
-  }
-
-  // ---- the prepared block: one contiguous run, two elements per load
-  {
-    struct alignas(2 * sizeof(T)) Pair { T lo, hi; };
-    const int used2 = (nblk * (nblk + 1) / 2) * kBlk / 2;  // kBlk is even
-    const Pair* const src = reinterpret_cast<const Pair*>(g.M);
-    Pair* const dst = reinterpret_cast<Pair*>(tri);
-    constexpr int MAX_IT = (NB * (NB + 1) / 2 * kBlk / 2 + kTriThreads - 1) / kTriThreads;
-    Pair v[MAX_IT];
+        for (int v = 0; v < 4; ++v) acc[s][v] = (s * kIb + 4 * l4 + v == slice * kIb + l15) ? T(1) : T(0);
+      if (nblk == NB) head_solve<T, true>(tri, kIb + 1, 1, nblk, lane, acc);
+      else head_solve<T, false>(tri, kIb + 1, 1, nblk, lane, acc);
+      const int cc = orig(slice * kIb + l15);
 #pragma unroll
-    for (int it = 0; it < MAX_IT; ++it) {
-      const int e = tid + it * kTriThreads;
-      v[it] = src[e < used2 ? e : used2 - 1];
-    }
+      for (int s = 0; s < NB; ++s) {
+        if (s < nblk) {
 #pragma unroll
-    for (int it = 0; it < MAX_IT; ++it) {
-      const int e = tid + it * kTriThreads;
-      if (e < used2) dst[e] = v[it];
-    }
-  }
-  __syncthreads();
-  if (!job_on) return;
-
-  if (nblk == NB) head_solve<T, true>(tri, kIb + 1, 1, nblk, lane, acc);
-  else head_solve<T, false>(tri, kIb + 1, 1, nblk, lane, acc);
-
-  if (l15 < t_valid) {
-#pragma unroll
-    for (int s = 0; s < NB; ++s) {
-      if (s < nblk) {
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int ii = orig(s * kIb + 4 * l4 + v);
-          if (ii < b) g.B[(int64_t)ii * ldb + t] = acc[s][v];
+          for (int v = 0; v < 4; ++v) {
+            const int rr = orig(s * kIb + 4 * l4 + v);
+            if (rr < b && cc < b) out[rr * kNbMax + cc] = acc[s][v];
+          }
         }
       }
     }
