@@ -138,6 +138,23 @@ def test_factor_then_solve_on_the_gpu(B, oracle, kind):
     assert max_rel_err(X, np.linalg.solve(A, rhs)) <= TOL64
 
 
+def test_cholesky_solve_with_a_condition_number_of_a_thousand(B, oracle):
+    """The device multiplies by explicitly inverted 128 x 128 diagonal blocks; their condition enters its
+    error.  Gram matrix + 1e-3 I (condition about 1.3e3, against about 2 for the workload recipe's + I):
+    the solution still matches the substitution of the oracle, and the system's residual stays small."""
+    n, nrhs = 700, 9
+    announce(f"solve chol n={n} nrhs={nrhs} shift 1e-3")
+    A = inputs.spd_matrix(n, 41)
+    A[np.diag_indices(n)] += 1e-3 - 1.0
+    F, info = oracle.cholesky(A)
+    assert info == 0
+    rhs = inputs.uniform_matrix(42, 3, n, nrhs)
+    want = oracle.cholesky_solve(F, rhs)
+    got = _gpu_solve(B, "chol", F, rhs)
+    assert max_rel_err(got, want) <= TOL64
+    assert np.abs(A @ got - rhs).max() <= 64 * n * EPS64 * np.abs(A).max() * np.abs(got).max()
+
+
 def test_n4000_sampled_columns(B, oracle):
     """The benchmark's matrix size: device factor, then the oracle's solve on that factor for a few columns."""
     n, nrhs = 4000, 64
