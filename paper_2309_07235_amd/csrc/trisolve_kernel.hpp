@@ -5,7 +5,8 @@
 // the chain of the substitution by inverting every diagonal block up front (this kernel: one
 // workgroup per block, all blocks at once, independent of the right-hand sides), so that each step of
 // the chain is two small products on the tiled GEMM: X_k = W_k * B_k, then the rows still open
-// -= (factor's block column k) * X_k.
+// -= (factor's block column k) * X_k.  The host pairs the 128-row inverses into inverses of 256-row
+// blocks (two more small products per pair, all pairs at once), which halves the steps of the chain.
 //
 // The inversion is the panel solve of the factorisations run on the identity: the block is brought
 // to the form head_solve takes, lower triangular M' with 16 x 16 sub-blocks whose diagonal ones are
@@ -54,13 +55,16 @@ __device__ inline void tri_inv16(const T (&a)[16], const T (&rdiag)[16], T (&x)[
   });
 }
 
-// One workgroup per diagonal block of the factor.
+// One workgroup per diagonal block of the factor.  Two consecutive blocks share a 256 x 256 area
+// of the output (row stride 256): block 2p at its top left, block 2p + 1 at its bottom right; the
+// host fills in the off-diagonal quarter that makes the area the inverse of the 256-row block.
+constexpr int kTriPair = 2 * kNbMax;
 template <typename T>
 struct TriPrepareArgs {
   const T* F;   // the factor (n x n, leading dimension lda)
   int64_t lda;
   int64_t n;
-  T* out;       // one 128 x 128 inverse per diagonal block
+  T* out;       // one kTriPair x kTriPair area per pair of diagonal blocks
 };
 
 template <typename T, int MODE>
@@ -138,10 +142,10 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
   __syncthreads();
 
   // ---- the block's inverse: the substitution run on the identity, 16 columns per wave and pass.
-  // out holds W = M^-1 for the block in its own (un-reversed) index space, 128 x 128 row-major, so
-  // that the solve itself is the plain product W * B; what lies outside the b x b block is never read.
+  // out holds W = M^-1 for the block in its own (un-reversed) index space, row-major, so that the
+  // solve itself is the plain product W * B; what lies outside the b x b block is never read.
   using acc_t = typename Mfma<T>::acc_t;
-  T* const out = g.out + (int64_t)blockIdx.x * (kNbMax * kNbMax);
+  T* const out = g.out + (int64_t)(blockIdx.x >> 1) * (kTriPair * kTriPair) + (blockIdx.x & 1) * (kNbMax * kTriPair + kNbMax);
   for (int pass = 0; pass < NB / (kTriThreads / 64); ++pass) {
     const int slice = pass * (kTriThreads / 64) + wave;
     if (slice < nblk) {  // uniform per wave
@@ -159,7 +163,7 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const int rr = orig(s * kIb + 4 * l4 + v);
-            if (rr < b && cc < b) out[rr * kNbMax + cc] = acc[s][v];
+            if (rr < b && cc < b) out[rr * kTriPair + cc] = acc[s][v];
           }
         }
       }
