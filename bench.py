@@ -140,12 +140,16 @@ def main() -> int:
     # ---- per-kernel figures and the GEMM-phase roofline (a repeat of the timed steps, one
     # kernel at a time, with per-launch events on the stream the GEMM runs on) -------------------
     def timed(fn, reps):
+        # device events on the caller's stream (every entry point joins its helper streams back into it):
+        # a wall clock would add the cost of the two synchronisations, which is not small against 20 short calls
         torch.cuda.synchronize()
-        t = time.perf_counter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for r in range(reps):
             fn(r)
+        e1.record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) / reps
+        return e0.elapsed_time(e1) * 1e-3 / reps
 
     def restore(bufs, src):
         for b in bufs:
