@@ -20,9 +20,11 @@
  *     work on hip_stream.  Some of its kernels are then launched before the
  *     kernel they depend on has finished and wait for it on counters in the
  *     workspace (a bounded poll), so two factorisations must not share one
- *     workspace while either is still running.  The helper streams and their events are shared by
- *     all calls of the process, so the entry points are not thread safe: calls
- *     from several host threads must be serialised by the caller.
+ *     workspace while either is still running.  The helper streams and their
+ *     events are shared by all calls of the process; a process-wide lock is held
+ *     while a factorisation enqueues its work, so calls from several host
+ *     threads are safe (each with a workspace of its own) and run one behind the
+ *     other on the helper streams.  The profiling switches are not thread safe.
  *   - Return value: DLA_SUCCESS (0); -i when the i-th argument (1-based) is
  *     invalid (null pointer, negative size, leading dimension too small,
  *     unknown dtype, misaligned pointer); or one of the positive DLA_ERR_*

@@ -4,6 +4,7 @@
 #include "factor_kernels.hpp"
 #include "update_kernel.hpp"
 #include "head_kernel.hpp"
+#include <mutex>
 #include "host_common.hpp"
 
 namespace dla {
@@ -170,7 +171,7 @@ struct LookaheadCtx {
   hipStream_t head = nullptr;   // head updates
   hipStream_t panel = nullptr;  // panel solves + strip updates
   hipStream_t bulk = nullptr;   // bulk trailing updates
-  hipEvent_t ev[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   bool ok = false;
 };
 static LookaheadCtx& lookahead_ctx() {
@@ -179,7 +180,7 @@ static LookaheadCtx& lookahead_ctx() {
     bool good = hipStreamCreateWithFlags(&ctx.head, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
-    for (int i = 0; i < 7 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 8 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
     ctx.ok = good;
   }
   return ctx;
@@ -336,6 +337,11 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     // Only the chain is handed over this way: a waiting kernel holds its compute units, and the
     // bulk update needs every unit outside the reserve at once, so a head update that also waited
     // in place for the strips (tried) doubled the bulk update's run time.
+    // The helper streams and events are shared by every call of the process: one call enqueues its
+    // whole pipeline before the next one starts to, so calls from several host threads line up on
+    // the helper streams instead of mixing their events.
+    static std::mutex submit_mutex;
+    std::lock_guard<std::mutex> submit_lock(submit_mutex);
     LookaheadCtx& ctx = lookahead_ctx();
     if (!ctx.ok) return DLA_ERR_HIP;
     hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_bulk = ctx.ev[2], e_start = ctx.ev[3], e_strip = ctx.ev[6];
@@ -441,6 +447,10 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     };
 
     chained = lookahead == 1;
+    // A call starts behind the previous pipelined call of the process: its first kernels would
+    // otherwise wait in place for work that is queued behind that call on the helper streams.
+    hipEvent_t e_call_done = ctx.ev[7];
+    if (hipStreamWaitEvent(st, e_call_done, 0) != hipSuccess) return DLA_ERR_HIP;
     hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, chain, 3);
     if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
     if (hipEventRecord(e_start, st) != hipSuccess || hipStreamWaitEvent(ctx.head, e_start, 0) != hipSuccess)
@@ -455,6 +465,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     if (hipStreamWaitEvent(st, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
     if (hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
     if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
+    if (hipEventRecord(e_call_done, st) != hipSuccess) return DLA_ERR_HIP;
   }
   if (KIND == KIND_CHOL && n > 1) {
     hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),

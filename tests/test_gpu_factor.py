@@ -409,6 +409,50 @@ def test_back_to_back_calls_share_the_helper_streams(B, oracle):
             _check_chol(oracle, to_host(d), H, n)
 
 
+def test_two_host_threads_factor_at_the_same_time(B, oracle):
+    """Two host threads, each with its own stream, matrices and workspace, call the factorisations at the same
+    time (the binding releases the interpreter lock inside the calls).  The library lines the calls up on its
+    shared helper streams; every result matches the oracle and no wait gives up."""
+    import threading
+    import torch
+    announce("two host threads factor concurrently")
+    jobs = [("lu", 1500, 70), ("chol", 1300, 71), ("lu", 900, 72), ("chol", 1000, 73)]
+    hosts = [inputs.general_dominant_matrix(n, s) if k == "lu" else inputs.spd_matrix(n, s) for k, n, s in jobs]
+    devs = [to_device(H) for H in hosts]
+    infos = [torch.full((1,), -99, dtype=torch.int32, device="cuda") for _ in jobs]
+    wss = [torch.empty(B.factor_workspace_bytes(n, B.DLA_F64, None), dtype=torch.uint8, device="cuda") for _, n, _ in jobs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(idx):
+        try:
+            st = torch.cuda.Stream()
+            for rep in range(3):
+                for j in idx:
+                    if rep:
+                        with torch.cuda.stream(st):
+                            devs[j].copy_(torch.from_numpy(hosts[j]).to("cuda"))
+                    fn = B.lu_factor if jobs[j][0] == "lu" else B.cholesky_factor
+                    fn(devs[j], None, workspace=wss[j], info=infos[j], stream=st)
+            st.synchronize()
+        except Exception as e:  # surfaced in the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(idx,)) for idx in ((0, 1), (2, 3))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for (kind, n, _), H, d, info in zip(jobs, hosts, devs, infos):
+        assert int(info.item()) == 0
+        if kind == "lu":
+            _check_lu(oracle, to_host(d), H, n)
+        else:
+            _check_chol(oracle, to_host(d), H, n)
+
+
 def test_a_wait_that_cannot_end_gives_up_and_is_reported(B, oracle):
     """The pipeline's in-kernel wait is bounded: with nothing to wait for, the kernel ends after the poll and
     reports -1 (forced from the host: the counter it polls is never touched; every wave exits normally).
