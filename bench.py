@@ -66,7 +66,7 @@ def mm3_flops(d):
     return 2.0 * (d["ni"] * d["nk"] * d["nj"] + d["nj"] * d["nm"] * d["nl"] + d["ni"] * d["nj"] * d["nl"])
 
 
-def main() -> int:
+def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -76,7 +76,7 @@ def main() -> int:
     ap.add_argument("--lookahead", type=int, default=None,
                     help="override the factorisations' look-ahead mode; 2 (pipeline ordered by stream events only) "
                          "is the one to use under a profiler that serialises kernels (rocprofv3 --pmc)")
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on ONE GPU; --gpus above 1 is not supported "
               "(no collectives or sharding are part of this build).", file=sys.stderr)
@@ -222,7 +222,7 @@ def main() -> int:
         "pct_of_measured_fp64_mfma_peak": round(gflops * 1e-3 / measured_peak * 100, 2),
         "kernels": kernels,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_F64_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH if n == N_FACTOR else None,
                      "kernel": "update_kernel (bulk trailing update of lu_factor and cholesky_factor, all launches)",
                      "launches": upd_launches, "avg_launch_ms": round(upd_ms / max(upd_launches, 1), 5),
                      "flops_per_launch": round(upd_fl / max(upd_launches, 1), 1),
