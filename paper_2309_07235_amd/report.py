@@ -92,18 +92,21 @@ def main(argv=None) -> int:
 
     # ---- 3mm ------------------------------------------------------------------------------------
     small = dict(ni=128, nk=128, nj=128, nm=128, nl=128)
-    for label, dims, tiles in (("3mm 128^3, all tiles 16x16", small, (16, 16, 0, 0, 0, 0)),
-                               ("3mm extralarge 1600x2000x1800x2400x2200", inputs.MM3_EXTRALARGE, None)):
-        ops = [torch.from_numpy(x).to(dev) for x in inputs.mm3_operands(4 if tiles is None else 1, **dims)]
-        g = torch.empty((dims["ni"], dims["nl"]), dtype=torch.float64, device=dev)
-        p = B.default_params(B.DLA_KERNEL_MM3, dims["nk"])
+    for label, dims, tiles, dtype in (("3mm 128^3, all tiles 16x16", small, (16, 16, 0, 0, 0, 0), "f64"),
+                                      ("3mm extralarge 1600x2000x1800x2400x2200", inputs.MM3_EXTRALARGE, None, "f64"),
+                                      ("3mm extralarge 1600x2000x1800x2400x2200 f32", inputs.MM3_EXTRALARGE, None, "f32")):
+        tdt = torch.float64 if dtype == "f64" else torch.float32
+        dt = B.DLA_F64 if dtype == "f64" else B.DLA_F32
+        ops = [torch.from_numpy(x).to(dev).to(tdt) for x in inputs.mm3_operands(4 if tiles is None else 1, **dims)]
+        g = torch.empty((dims["ni"], dims["nl"]), dtype=tdt, device=dev)
+        p = B.default_params(B.DLA_KERNEL_MM3, dims["nk"], dt)
         if tiles is not None:
             p = B.Mm3Params(B.GemmParams(*tiles), B.GemmParams(*tiles), B.GemmParams(*tiles))
-        ws = torch.empty(B.mm3_workspace_bytes(dims["ni"], dims["nj"], dims["nl"], B.DLA_F64), dtype=torch.uint8, device=dev)
+        ws = torch.empty(B.mm3_workspace_bytes(dims["ni"], dims["nj"], dims["nl"], dt), dtype=torch.uint8, device=dev)
         fl = 2.0 * (dims["ni"] * dims["nk"] * dims["nj"] + dims["nj"] * dims["nm"] * dims["nl"] + dims["ni"] * dims["nj"] * dims["nl"])
         fn = lambda: B.mm3(*ops, g, p, workspace=ws)
         med, mn = _time_calls(torch, fn, lambda: None, args.warmup, args.calls)
-        _line(label, fl, med, mn, "f64", peaks["f64"], _phases(B, torch, fn, lambda: None, args.calls))
+        _line(label, fl, med, mn, dtype, peaks[dtype], _phases(B, torch, fn, lambda: None, args.calls))
 
     # ---- factorisations ---------------------------------------------------------------------------
     def factor_case(kind, n, nb, dtype, seed):
