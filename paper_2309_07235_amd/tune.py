@@ -35,6 +35,10 @@ from typing import Callable, Dict, List, Optional, Sequence, Tuple
 Config = Tuple[int, ...]  # one index per parameter into that parameter's value list
 
 
+def _plain(x):
+    return tuple(x) if isinstance(x, (list, tuple)) else x
+
+
 @dataclass
 class SearchSpace:
     """Ordinal parameters: names[i] takes one of values[i]; a configuration is a tuple of indices."""
@@ -47,6 +51,10 @@ class SearchSpace:
 
     def decode(self, cfg: Config) -> Dict[str, object]:
         return {n: v[i] for n, v, i in zip(self.names, self.values, cfg)}
+
+    def encode(self, point: Dict[str, object]) -> Config:
+        """Inverse of decode; raises ValueError when a value is not in its parameter's list."""
+        return tuple(list(map(_plain, v)).index(_plain(point[n])) for n, v in zip(self.names, self.values))
 
     def features(self, cfg: Config) -> List[float]:
         """What the surrogate sees: numeric values as they are, tuples of numbers (a schedule of the menu:
@@ -199,7 +207,8 @@ def mm3_problem(dims: Dict[str, int], seed: int = 4, reps: int = 5, dtype: str =
         p = B.Mm3Params(B.GemmParams(*cfg["e"]), B.GemmParams(*cfg["f"]), B.GemmParams(*cfg["g"]))
         return _time_ms(lambda: B.mm3(*ops, g, p, workspace=ws), reps)
 
-    return space, objective
+    d = B.default_params(B.DLA_KERNEL_MM3, dims["nk"], dt)
+    return space, objective, {"e": d.e.as_tuple(), "f": d.f.as_tuple(), "g": d.g.as_tuple()}
 
 
 def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str = "f64"):
@@ -229,7 +238,8 @@ def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str =
 
         return _time_ms(call, reps)
 
-    return space, objective
+    d = B.default_params(B.DLA_KERNEL_LU if kind == "lu" else B.DLA_KERNEL_CHOLESKY, n, dt)
+    return space, objective, {"nb": d.nb, "lookahead": d.lookahead, "update": d.update.as_tuple()}
 
 
 def main(argv=None) -> int:
@@ -241,16 +251,21 @@ def main(argv=None) -> int:
     ap.add_argument("--strategy", choices=["rf", "random"], default="rf")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--db", default=None, help="CSV file for the performance database")
+    ap.add_argument("--from-default", action="store_true",
+                    help="spend the first evaluation on the library's default configuration, so that the result is "
+                         "never worse than it (the paper's searches start from random points)")
     args = ap.parse_args(argv)
 
     from . import inputs
     t0 = time.perf_counter()
     if args.kernel == "mm3":
         dims = inputs.MM3_EXTRALARGE if args.dataset == "extralarge" else inputs.MM3_SMALL
-        space, objective = mm3_problem(dims)
+        space, objective, default = mm3_problem(dims)
     else:
-        space, objective = factor_problem("lu" if args.kernel == "lu" else "chol", args.n)
+        space, objective, default = factor_problem("lu" if args.kernel == "lu" else "chol", args.n)
     db = PerformanceDatabase(space, args.db)
+    if args.from_default and args.evals > 0:
+        db.record(space.encode(default), float(objective(default)))
     search = surrogate_search if args.strategy == "rf" else random_search
     search(space, objective, args.evals, seed=args.seed, db=db)
     cfg, ms = db.best()

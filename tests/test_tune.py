@@ -31,6 +31,15 @@ def test_space_decode_size_and_legality():
     assert sp.sample(rng, seen, tries=200) is None
 
 
+def test_encode_is_the_inverse_of_decode():
+    space = tune.SearchSpace(["a", "t"], [[16, 32, 48], [(0, 0), (64, 64), (128, 64)]])
+    for cfg in [(0, 0), (2, 1), (1, 2)]:
+        assert space.encode(space.decode(cfg)) == cfg
+    assert space.encode({"a": 32, "t": [128, 64]}) == (1, 2)  # lists and tuples name the same value
+    with pytest.raises(ValueError):
+        space.encode({"a": 20, "t": (0, 0)})
+
+
 def test_random_search_is_seeded_distinct_and_stops_when_exhausted():
     sp = _bowl_space()
     a = tune.random_search(sp, _bowl, 40, seed=3)
