@@ -193,7 +193,9 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
  *   lower == 1:  lower(C) -= L*L^T in blocks of 128 rows: row block i is updated in columns
  *                0 .. 128*(i+1)-1, so the part of diagonal blocks above the diagonal changes too;
  *                d_r is ignored                                          (Cholesky)
- * k <= 128.  All three matrices share the leading dimension ld (they are parts of one matrix in the
+ * k <= 256: up to 128 one panel of the factorisation; above that the form the factorisations use
+ * for large trailing matrices, two panels at once (column blocks of 16 instead of 32, twice the
+ * flops per byte of C).  All three matrices share the leading dimension ld (they are parts of one matrix in the
  * factorisations).  C must not overlap L or R.
  */
 int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int64_t ld, int64_t m, int64_t k,

@@ -359,7 +359,7 @@ int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int6
                     dla_dtype dt, void* hip_stream) {
   if (lower != 0 && lower != 1) return -1;
   if (m < 0) return -6;
-  if (k < 0 || k > 128) return -7;
+  if (k < 0 || k > 256) return -7;
   if (dt != DLA_F64 && dt != DLA_F32) return -8;
   if (m > kMaxDim) return DLA_ERR_TOO_LARGE;
   if (m == 0 || k == 0) return DLA_SUCCESS;

@@ -12,6 +12,9 @@ namespace dla {
 constexpr int kNumCu = 256;   // compute units of an MI355X
 constexpr int kChainCu = 32;  // left to the latency chain while a bulk update runs
 constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot gets at least this many
+// Trailing matrices of at least this many rows run their bulk updates two panels at a time (measured:
+// below these sizes the step is bound by the latency chain and the deeper strips only lengthen it).
+constexpr int64_t kDeferMinRowsLu = 3072, kDeferMinRowsChol = 4096;
 
 static inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -66,13 +69,13 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = n
 }
 
 // Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp).
-template <typename T, int KIND, int NCB>
+template <typename T, int KIND, int NCB, int KMAX = kUpdKMax>
 static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
                              hipStream_t st, hipEvent_t done) {
   constexpr bool LOWER = (KIND == KIND_CHOL);
   constexpr int COLS = NCB * 16;
-  auto kern = update_kernel<T, LOWER, NCB>;
-  using LD = UpdateLds<T, LOWER, NCB>;
+  auto kern = update_kernel<T, LOWER, NCB, KMAX>;
+  using LD = UpdateLds<T, LOWER, NCB, KMAX>;
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -115,6 +118,8 @@ template <typename T, int KIND>
 static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
                          hipStream_t st, hipEvent_t done = nullptr) {
   if (m <= 0) return DLA_SUCCESS;
+  // depth above 128 (two panels at once): the left panel takes twice the registers, the column blocks are 16 wide
+  if (b > kUpdKMax) return launch_update_ncb<T, KIND, 1, 2 * kUpdKMax>(L, R, C, ld, m, b, skip, slots, st, done);
   const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
   int64_t wide_blocks = 0;
   for (int p = 0; p < npanels; ++p) wide_blocks += update_blocks_of_panel(p, (int)m, KIND == KIND_CHOL, 64);
@@ -349,6 +354,13 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     constexpr int SOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT;
     const int nsteps = (int)((n + nb - 1) / nb) - 1;  // steps that have a panel behind the diagonal block
     bool bulk_pending = false;
+    // Two-level blocking of the bulk update while the trailing matrix is large (the bulk stream is then the
+    // longest): every other step puts its bulk update off (owed), and the step after it carries both
+    // panels as one update of depth 2 nb, which halves the traffic of the trailing matrix per flop.  So
+    // that nothing on the side path has to wait for that longer update, the strips of such a wide step
+    // also take block row / column N2 and block (N3,N3), and its bulk update starts behind them; the
+    // next step's strips then touch nothing the bulk update writes (after_wide).
+    bool owed = false, after_wide = false;
 
     // ---- panel and bulk streams of one step
     auto panel_side = [&](int step) -> int {
@@ -362,12 +374,16 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       const int64_t bn = m < nb ? m : nb;     // size of block N
       const int64_t mr = m - bn;              // what is left behind it
       const int64_t bn2 = mr < nb ? mr : nb;  // size of block N2
+      const bool wide = owed;                 // this step also applies the previous step's panels
+      const int ksh = wide ? nb : 0;          // depth added in front of this step's panels
+      const int kk = b + ksh;
+      const int64_t lsh = ksh, ush = (KIND == KIND_LU) ? (int64_t)ksh * lda : (int64_t)ksh;
       int r;
       if (hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
       // the last kernel of the step on this stream carries e_strip
       if ((r = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return r;
       if (mr > 0) {
-        if (bulk_pending && hipStreamWaitEvent(ctx.panel, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
+        if (bulk_pending && !after_wide && hipStreamWaitEvent(ctx.panel, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
         const T* Lr = L21 + bn * lda;  // rows behind block N of the solved column panel
         const GemmSchedule ps = panel_schedule(mr);
         GemmGroup<T> g;
@@ -375,11 +391,11 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         double flops = 0.0;
         auto add = [&](const T* a, const T* bm, T* c, int64_t M, int64_t N, T* copy) {
           if (M <= 0 || N <= 0) return;
-          g.prob[np] = make_problem<T>(ps, SOP, a, lda, bm, lda, c, lda, M, N, b, tiles);
+          g.prob[np] = make_problem<T>(ps, SOP, a - lsh, lda, bm - ush, lda, c, lda, M, N, kk, tiles);
           g.prob[np].C2 = copy;
           g.prob[np].ldc2 = kNbMax;
           tiles += problem_tiles(ps, SOP, g.prob[np]);
-          flops += 2.0 * (double)M * (double)N * (double)b;
+          flops += 2.0 * (double)M * (double)N * (double)kk;
           ++np;
         };
         const int64_t rest = mr - bn2;  // rows / columns behind block N2
@@ -396,21 +412,56 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
           add(Lr + bn2 * lda, L21, A22 + (bn + bn2) * lda, rest, bn, nullptr);           // block column N below it
           add(Lr, Lr, A22 + bn * lda + bn, bn2, bn2, nullptr);                           // block (N2,N2)
         }
-        for (int q = np; q < kMaxGroup; ++q) g.prob[q] = g.prob[0];
-        g.nprob = np;
-        g.total_tiles = tiles;
-        {
+        auto launch_group = [&](hipEvent_t done) -> int {
+          if (np == 0) return DLA_SUCCESS;
+          for (int q = np; q < kMaxGroup; ++q) g.prob[q] = g.prob[0];
+          g.nprob = np;
+          g.total_tiles = tiles;
           ProfileScope scope(PHASE_GEMM, flops, ctx.panel);
-          tl_gemm_done_event = e_strip;
-          if ((r = launch_gemm<T>(ps, SOP, g, ctx.panel)) != DLA_SUCCESS) return r;
+          tl_gemm_done_event = done;
+          const int rr = launch_gemm<T>(ps, SOP, g, ctx.panel);
+          np = tiles = 0;
+          flops = 0.0;
+          return rr;
+        };
+        if ((r = launch_group(e_strip)) != DLA_SUCCESS) return r;
+        if (wide) {
+          // block row / column N2 behind block (N2,N2), and block (N3,N3): what the next step's strips work on
+          const int64_t bn3 = rest < nb ? rest : nb, o2 = bn + bn2;
+          const T* Lr3 = Lr + bn2 * lda;  // rows from block N3 on
+          if (KIND == KIND_LU) {
+            add(Lr3, U12 + bn, A22 + o2 * lda + bn, rest, bn2, nullptr);       // block column N2 below (N2,N2)
+            add(Lr, U12 + o2, A22 + bn * lda + o2, bn2, rest, nullptr);         // block row N2 right of it
+            add(Lr3, U12 + o2, A22 + o2 * lda + o2, bn3, bn3, nullptr);         // block (N3,N3)
+          } else {
+            add(Lr3, Lr, A22 + o2 * lda + bn, rest, bn2, nullptr);              // block column N2 below (N2,N2)
+            add(Lr3, Lr3, A22 + o2 * lda + o2, bn3, bn3, nullptr);              // block (N3,N3)
+          }
+          if ((r = launch_group(nullptr)) != DLA_SUCCESS) return r;
         }
       }
       if (mr > bn2) {
+        const int64_t rest = mr - bn2;
+        // put the bulk update off when the step after this one can carry it: full blocks N2, N3 and
+        // two more behind them, and a trailing matrix large enough for the bulk stream to be the longest
+        if (!owed && auto_tile && nb == kNbMax && mr >= (KIND == KIND_LU ? kDeferMinRowsLu : kDeferMinRowsChol) && rest >= 4 * (int64_t)nb) {
+          owed = true;
+          after_wide = false;
+          return DLA_SUCCESS;
+        }
         if (hipStreamWaitEvent(ctx.bulk, e_solve, 0) != hipSuccess) return DLA_ERR_HIP;
-        if ((r = trailing(L21 + bn * lda, U12 + bn, A22 + bn * lda + bn, mr, b, (int)bn2, ctx.bulk, e_bulk)) != DLA_SUCCESS)
+        if (wide) {
+          const int64_t bn3 = rest < nb ? rest : nb, o2 = bn + bn2;
+          if ((r = trailing(L21 + o2 * lda - lsh, U12 + o2 - ush, A22 + o2 * lda + o2, rest, kk, (int)bn3, ctx.bulk, e_bulk)) !=
+              DLA_SUCCESS)
+            return r;
+        } else if ((r = trailing(L21 + bn * lda, U12 + bn, A22 + bn * lda + bn, mr, b, (int)bn2, ctx.bulk, e_bulk)) != DLA_SUCCESS) {
           return r;
+        }
         bulk_pending = true;
       }
+      owed = false;
+      after_wide = wide;
       return DLA_SUCCESS;
     };
 

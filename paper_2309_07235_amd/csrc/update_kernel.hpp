@@ -48,12 +48,12 @@ struct UpdateArgs {
   int skip;     // the leading skip x skip block of C (skip: multiple of 16) is not written: another stream owns it
 };
 
-template <typename T, bool LOWER, int NCB>
+template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax>
 struct UpdateLds {
   // The b x cols right-operand block is stored in MFMA fragment order: element (k, col) sits at
   // ((k/4)*NCB + col/16)*64 + (k%4)*16 + col%16, i.e. the 64 values one wave reads for k-step k/4 and
   // column block col/16 are contiguous in lane order, so fragment reads are conflict free.
-  static constexpr int B_ELEMS = kUpdKMax * NCB * 16;
+  static constexpr int B_ELEMS = KMAX * NCB * 16;
   static constexpr int B_PAD = B_ELEMS;
   // the left panel is staged through the same memory, 64 k-columns at a time: [rows][65]
   static constexpr int A_HALF = kUpdRows * 65;
@@ -70,12 +70,13 @@ __host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool
   return (update_blocks_of_panel(p, m, lower, cols) + bpi - 1) / bpi;
 }
 
-template <typename T, bool LOWER, int NCB>
+template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax>
 __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
+  static_assert(KMAX % 64 == 0 && kUpdThreads % KMAX == 0, "depth");
   using acc_t = typename Mfma<T>::acc_t;
-  using LD = UpdateLds<T, LOWER, NCB>;
+  using LD = UpdateLds<T, LOWER, NCB, KMAX>;
   constexpr int kUpdCols = NCB * 16;  // columns per iteration
-  constexpr int KSTEPS = kUpdKMax / 4;  // 32
+  constexpr int KSTEPS = KMAX / 4;    // 32 or 64
   extern __shared__ __align__(16) unsigned char smem_raw[];
   T* const smem = reinterpret_cast<T*>(smem_raw);
 
@@ -112,7 +113,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   T afrag[KSTEPS];
   const int wrow0 = row0 + wave * 16;  // first row of this wave
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
+  for (int half = 0; half < KMAX / 64; ++half) {  // 64 k-columns per pass
     {  // rows x 64 k-columns: thread -> (row, 2 adjacent columns); the threads cover RPP rows per pass
       constexpr int RPP = kUpdThreads / 32, PASSES = kUpdRows / RPP;
       static_assert(PASSES == 8, "staging registers");
@@ -138,19 +139,21 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
     }
     lds_barrier();
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS / 2; ++kk)
-      afrag[half * (KSTEPS / 2) + kk] = smem[(wave * 16 + l15) * 65 + kk * 4 + l4];
+    for (int kk = 0; kk < 16; ++kk)
+      afrag[half * 16 + kk] = smem[(wave * 16 + l15) * 65 + kk * 4 + l4];
     lds_barrier();
   }
 
   // ---- right-operand block loader: b x 32 block starting at column j0 -> registers -> LDS ------
   // LU:       rows k of U12, cols contiguous columns: thread -> (k = tid / 4, cols / 4 columns)
   // Cholesky: rows j0..j0+cols-1 of L21, b contiguous k: thread -> (row = tid % cols, BPT k-values)
-  constexpr int BPT = kUpdKMax * kUpdCols / kUpdThreads;  // 8 or 16 elements per thread
+  constexpr int BPT = KMAX * kUpdCols / kUpdThreads;  // 8 or 16 elements per thread
+  constexpr int TPK = kUpdThreads / KMAX;             // LU: threads that share one k-row of the block
+  static_assert(TPK * BPT == kUpdCols && BPT <= 16 && 16 % BPT == 0, "right-operand staging");
   T bst[BPT];
   auto fetch_b = [&](int j0) {
     if (!LOWER) {
-      const int k = tid >> 2, c0 = (tid & 3) * BPT;
+      const int k = tid / TPK, c0 = (tid % TPK) * BPT;
       const T* p = g.R + (int64_t)(k < b ? k : b - 1) * ld;
       const bool full = (j0 + kUpdCols <= m) && (k < b);
       if (full) {
@@ -185,7 +188,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   auto stash_b = [&](int buf) {
     T* sb = smem + buf * LD::B_PAD;
     if (!LOWER) {
-      const int k = tid >> 2, c0 = (tid & 3) * BPT;  // BPT consecutive columns inside one 16-column block
+      const int k = tid / TPK, c0 = (tid % TPK) * BPT;  // BPT consecutive columns inside one 16-column block
       T* d = sb + ((k >> 2) * NCB + (c0 >> 4)) * 64 + (k & 3) * 16 + (c0 & 15);
 #pragma unroll
       for (int i = 0; i < BPT; ++i) d[i] = bst[i];

@@ -169,7 +169,7 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.dla_rank_update(1, fake, None, None, 256, 64, 16, B.DLA_F64, None) == -4
     assert L.dla_rank_update(0, fake, fake, fake, 32, 64, 16, B.DLA_F64, None) == -5
     assert L.dla_rank_update(0, fake, fake, fake, 256, -1, 16, B.DLA_F64, None) == -6
-    assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 129, B.DLA_F64, None) == -7
+    assert L.dla_rank_update(0, fake, fake, fake, 512, 64, 257, B.DLA_F64, None) == -7
     assert L.dla_rank_update(0, fake, fake, fake, 256, 64, 16, 5, None) == -8
     assert L.dla_rank_update(0, fake, fake, fake, 256, 0, 16, B.DLA_F64, None) == 0
     tf = ctypes.c_double()

@@ -200,6 +200,26 @@ def test_n8192_properties(B, oracle):
         y0 = oracle.symv_lower(A, x)
         y1 = oracle.cholesky_apply(L, x)
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS64 * np.linalg.norm(y0)
+    announce("N=8192 Cholesky against the oracle's full factorisation")
+    want, _ = oracle.cholesky(A)
+    assert max_rel_err(L, want) <= TOL64
+
+
+@pytest.mark.parametrize("kind,n", [("lu", 5000), ("lu", 3500), ("chol", 6100), ("chol", 4700)])
+def test_sizes_around_the_two_level_bulk_update(B, oracle, kind, n):
+    """Large trailing matrices take their bulk updates two panels at a time; these sizes start and end that
+    regime at different step parities and have a ragged last block.  Element by element against the oracle."""
+    announce(f"two-level {kind} n={n}")
+    if kind == "lu":
+        A = inputs.diag_dominant_matrix(n, 81)
+        got, info = _gpu_lu(B, A)
+        assert info == 0
+        _check_lu(oracle, got, A, n)
+    else:
+        A = inputs.spd_matrix(n, 82)
+        got, info = _gpu_chol(B, A)
+        assert info == 0
+        _check_chol(oracle, got, A, n)
 
 
 # ------------------------------------------------------------------ schedules
@@ -353,11 +373,12 @@ def test_n8192_fp32_properties(B, oracle):
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS32 * np.linalg.norm(y0)
 
 
-@pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96)])
+@pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96),
+                                 (300, 256), (1000, 200), (777, 144)])  # depth above 128: the two-panel form
 @pytest.mark.parametrize("lower", [False, True])
 def test_rank_update_alone(B, oracle, m, k, lower):
     """dla_rank_update (the bulk trailing update on its own) against the oracle's plain product (the E of a
-    3mm whose second product is empty-sized): ragged row panels, ragged 32-column blocks, partial k."""
+    3mm whose second product is empty-sized): ragged row panels, ragged column blocks, partial k."""
     import torch
     announce(f"rank_update m={m} k={k} lower={lower}")
     n = m + k
