@@ -27,14 +27,24 @@ METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
 # HBM bytes per launch of the bulk update kernel (fetch + write), from the two rocprofv3 --pmc passes
 # summarised in profiles/update_kernel_hbm_traffic_n4000.txt (counter readings scaled by the same
 # counters' readings for a device copy of known size).  None until measured.
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 74550 * 1024
+UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 67239 * 1024
 
 
 def update_algorithmic_bytes(n, nb=128, lower=False):
     """(launches, bytes) the bulk updates of one factorisation must move: every element of the region
-    read and written once, the two panels read once (blocks of 128 rows for the lower-triangular case)."""
+    read and written once, the panels read once (blocks of 128 rows for the lower-triangular case).
+    Mirrors the library's schedule: while the trailing matrix is large (3072 rows for LU, 4096 for
+    Cholesky, block size 128) every other step puts its bulk update off and the next one applies both
+    panels at once, to the region behind block N3."""
+    def region(rows, lead):
+        if lower:
+            elems = sum(min(128, rows - r0) * min(r0 + 128, rows) for r0 in range(0, rows, 128))
+        else:
+            elems = rows * rows
+        return elems - lead * lead
+
     launches, total = 0, 0
-    k0 = 0
+    k0, owed = 0, False
     while True:
         m = n - k0 - nb
         if m <= 0:
@@ -43,13 +53,14 @@ def update_algorithmic_bytes(n, nb=128, lower=False):
         mr = m - bn
         bn2 = min(nb, mr)
         if mr > bn2:
-            if lower:
-                elems = sum(min(128, mr - r0) * min(r0 + 128, mr) for r0 in range(0, mr, 128))
+            rest = mr - bn2
+            if not owed and nb == 128 and mr >= (4096 if lower else 3072) and rest >= 4 * nb:
+                owed = True
             else:
-                elems = mr * mr
-            elems -= bn2 * bn2
-            total += 8 * (2 * elems + (1 if lower else 2) * mr * nb)
-            launches += 1
+                rows, depth, lead = (rest, 2 * nb, min(nb, rest)) if owed else (mr, nb, bn2)
+                total += 8 * (2 * region(rows, lead) + (1 if lower else 2) * rows * depth)
+                launches += 1
+                owed = False
         k0 += nb
     return launches, total
 

@@ -20,6 +20,13 @@
 //     result, fetches its share of the next right-operand block and its next C block, and writes
 //     the share to LDS; two barriers per block keep the groups in anti-phase.
 //
+// Two depths are instantiated (KMAX).  128: one panel of the factorisation, as above.  256: two
+// panels at once, the form the factorisations use while the trailing matrix is large -- every
+// element of C then carries 4*128 flops per read and write, 32 flop/byte, which takes the update
+// off the memory bound.  The left panel then fills 128 registers per lane, so the column blocks
+// are 16 wide (NCB = 1: one accumulator block per wave and set); MFMAs per wave and iteration,
+// right-operand bytes per iteration and the pipeline are the same as at depth 128 with NCB = 2.
+//
 // Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone.
 #pragma once
 #include <type_traits>
@@ -34,7 +41,7 @@ namespace dla {
 
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
 constexpr int kUpdThreads = 512;
-constexpr int kUpdKMax = 128;   // largest block size b
+constexpr int kUpdKMax = 128;   // largest block size b (depth of one panel)
 
 template <typename T>
 struct UpdateArgs {
