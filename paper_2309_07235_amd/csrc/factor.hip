@@ -119,7 +119,12 @@ static int launch_update(const T* L, const T* R, T* C, int64_t ld, int64_t m, in
                          hipStream_t st, hipEvent_t done = nullptr) {
   if (m <= 0) return DLA_SUCCESS;
   // depth above 128 (two panels at once): the left panel takes twice the registers, the column blocks are 16 wide
-  if (b > kUpdKMax) return launch_update_ncb<T, KIND, 1, 2 * kUpdKMax>(L, R, C, ld, m, b, skip, slots, st, done);
+  if (b > kUpdKMax) {
+    // fp32 has the registers for 32-column blocks next to the deeper left panel (rows of C in 128-byte pieces, as
+    // fp64; 64-column blocks were measured and are slower: LU 6.10 against 6.03 ms at N = 8192)
+    if constexpr (sizeof(T) == 4) return launch_update_ncb<T, KIND, 2, 2 * kUpdKMax>(L, R, C, ld, m, b, skip, slots, st, done);
+    else return launch_update_ncb<T, KIND, 1, 2 * kUpdKMax>(L, R, C, ld, m, b, skip, slots, st, done);
+  }
   const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
   int64_t wide_blocks = 0;
   for (int p = 0; p < npanels; ++p) wide_blocks += update_blocks_of_panel(p, (int)m, KIND == KIND_CHOL, 64);

@@ -24,8 +24,9 @@
 // panels at once, the form the factorisations use while the trailing matrix is large -- every
 // element of C then carries 4*128 flops per read and write, 32 flop/byte, which takes the update
 // off the memory bound.  The left panel then fills 128 registers per lane, so the column blocks
-// are 16 wide (NCB = 1: one accumulator block per wave and set); MFMAs per wave and iteration,
-// right-operand bytes per iteration and the pipeline are the same as at depth 128 with NCB = 2.
+// are 16 wide in fp64 (NCB = 1: one accumulator block per wave and set; fp32 keeps NCB = 2); MFMAs per
+// wave and iteration, right-operand bytes per iteration and the pipeline are the same as at depth 128
+// with NCB = 2.
 //
 // Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone.
 #pragma once
