@@ -238,8 +238,8 @@ def main(argv=None) -> int:
                      "launches": upd_launches, "avg_launch_ms": round(upd_ms / max(upd_launches, 1), 5),
                      "flops_per_launch": round(upd_fl / max(upd_launches, 1), 1),
                      "algorithmic_bytes_per_launch": round(alg_bytes / max(alg_launches, 1), 1),
-                     "how": "per-launch HIP events on the stream the kernel runs on, in a repeat of the timed steps "
-                            "with the other streams of the pipeline running beside it"},
+                     "how": "HIP start/stop events attached to every launch of the kernel (hipExtLaunchKernelGGL) on the "
+                            "stream it runs on, in a repeat of the timed steps with the pipeline's other streams beside it"},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

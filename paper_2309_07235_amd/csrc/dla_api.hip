@@ -110,6 +110,21 @@ int profile_begin(int phase, double flops, hipStream_t st) {
   return (int)g_records.size() - 1;
 }
 
+bool profile_kernel_events(int phase, double flops, hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_profile_on) return false;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  ProfileRecord r;
+  r.e0 = take_event();
+  r.e1 = take_event();
+  r.phase = phase;
+  r.flops = flops;
+  if (!r.e0 || !r.e1) return false;
+  g_records.push_back(r);
+  *start = r.e0;
+  *stop = r.e1;
+  return true;
+}
+
 void profile_end(int slot, hipStream_t st) {
   if (slot < 0) return;
   std::lock_guard<std::mutex> lock(g_profile_mutex);

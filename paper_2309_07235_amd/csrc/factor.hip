@@ -106,7 +106,14 @@ static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m
   }
   a.items = items;
   const double flops = (LOWER ? 1.0 : 2.0) * ((double)m * (double)m - (double)skip * (double)skip) * (double)b;
-  ProfileScope scope(PHASE_UPDATE, flops, st);
+  hipEvent_t p0 = nullptr, p1 = nullptr;
+  if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
+    // profiling: the dispatch carries the profiler's start / stop events, the completion event follows it
+    hipExtLaunchKernelGGL(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, p0, p1, 0, a);
+    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    if (done && hipEventRecord(done, st) != hipSuccess) return DLA_ERR_HIP;
+    return DLA_SUCCESS;
+  }
   launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }

@@ -52,6 +52,11 @@ int run_gemm(const GemmSchedule& s, int op, const T* A, int64_t lda, const T* B,
 int profile_begin(int phase, double flops, hipStream_t st);
 void profile_end(int slot, hipStream_t st);
 
+// For a launch that can carry its own start / stop events (hipExtLaunchKernelGGL): a record whose two
+// events the caller attaches to the kernel's dispatch, so that the record holds the kernel's own
+// duration, as a kernel trace reports it.  False when profiling is off.
+bool profile_kernel_events(int phase, double flops, hipEvent_t* start, hipEvent_t* stop);
+
 struct ProfileScope {
   int slot;
   hipStream_t st;
