@@ -283,6 +283,10 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   // a compute unit's registers, so the small kernels of the latency chain (diagonal block, head
   // update) would otherwise queue behind a whole bulk update.
   const bool pipelined = lookahead && n > 2 * (int64_t)nb;
+  // Cholesky's zero upper triangle can be written early when nothing dirties it later: the default update
+  // kernel works on 128-row panels and stays inside the 128-wide block diagonal; other block sizes or a tiled
+  // update write above it, and the triangle is zeroed at the end instead.
+  const bool early_zero = KIND == KIND_CHOL && pipelined && nb == kUpdRows && auto_tile;
   const int slots = pipelined ? kNumCu - kChainCu : kNumCu;
   auto trailing_gemm = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, int skip, hipStream_t s) -> int {
     const GemmSchedule us = update_schedule(mm);
@@ -519,6 +523,14 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     if (hipEventRecord(e_start, st) != hipSuccess || hipStreamWaitEvent(ctx.head, e_start, 0) != hipSuccess)
       return DLA_ERR_HIP;
     if ((rc = diag(0, 0, st, chained ? nullptr : e_diag[0])) != DLA_SUCCESS) return rc;
+    if (early_zero) {
+      // the output's zero upper triangle: the blocks above the block diagonal now, on the panel stream, beside
+      // the first steps (nothing reads or writes them); each diagonal block's own upper part by its kernel
+      if (hipStreamWaitEvent(ctx.panel, e_start, 0) != hipSuccess) return DLA_ERR_HIP;
+      hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),
+                         dim3(256), 0, ctx.panel, A, lda, (int)n, nb);
+      if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    }
 
     for (int step = 0; step < nsteps; ++step) {
       if ((rc = chain_side(step)) != DLA_SUCCESS) return rc;
@@ -530,9 +542,9 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
     if (hipEventRecord(e_call_done, st) != hipSuccess) return DLA_ERR_HIP;
   }
-  if (KIND == KIND_CHOL && n > 1) {
+  if (KIND == KIND_CHOL && n > 1 && !early_zero) {
     hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),
-                       dim3(256), 0, st, A, lda, (int)n);
+                       dim3(256), 0, st, A, lda, (int)n, 1);
     if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
   }
   return DLA_SUCCESS;

@@ -478,10 +478,10 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
     // 4 waves = 256 threads: thread = two adjacent columns, 4 rows per pass
     const int t = tid - 256;
     const int c = (t % (kNbMax / 2)) * 2, r0 = t / (kNbMax / 2);
-    for (int r = r0; r < b; r += 4) {
+    for (int r = r0; r < b; r += 4) {  // Cholesky: zeros above the diagonal (the output convention)
       T* p = g.A + (int64_t)r * g.lda + c;
-      if (c < b && (KIND == KIND_LU || c <= r)) p[0] = S[r * kSld + c];
-      if (c + 1 < b && (KIND == KIND_LU || c + 1 <= r)) p[1] = S[r * kSld + c + 1];
+      if (c < b) p[0] = (KIND == KIND_LU || c <= r) ? S[r * kSld + c] : T(0);
+      if (c + 1 < b) p[1] = (KIND == KIND_LU || c + 1 <= r) ? S[r * kSld + c + 1] : T(0);
     }
   }
   DLA_TRACE(20);
@@ -510,12 +510,14 @@ static __global__ void identity16_kernel(double* a, int* counters) {
   if (t < 3) counters[t] = 0;
 }
 
-// Zero the strict upper triangle (Cholesky output convention).
+// Zero the strict upper triangle (Cholesky output convention).  nb = 1: all of it.  nb > 1: only the
+// blocks above the block diagonal of width nb, which no kernel of the factorisation touches, so that
+// this can run beside the first steps; the diagonal-block kernel zeroes its own block's upper part.
 template <typename T>
-__global__ void __launch_bounds__(256) zero_upper_kernel(T* A, int64_t lda, int n) {
+__global__ void __launch_bounds__(256) zero_upper_kernel(T* A, int64_t lda, int n, int nb) {
   const int col = (int)blockIdx.x * 256 + (int)threadIdx.x;
   for (int row = (int)blockIdx.y; row < n; row += (int)gridDim.y)
-    if (col > row && col < n) A[(int64_t)row * lda + col] = T(0);
+    if (col >= (row / nb + 1) * nb && col < n) A[(int64_t)row * lda + col] = T(0);
 }
 
 }  // namespace dla
