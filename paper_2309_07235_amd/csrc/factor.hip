@@ -15,6 +15,9 @@ constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot ge
 // Trailing matrices of at least this many rows run their bulk updates two panels at a time (measured:
 // below these sizes the step is bound by the latency chain and the deeper strips only lengthen it).
 constexpr int64_t kDeferMinRowsLu = 3072, kDeferMinRowsChol = 4096;
+// Cholesky updates of at least this many rows use work items that cross row panels (measured: 3-18 %
+// faster from 6000 rows on, slower below 4000; inside the pipeline it pays from about 8000 rows).
+constexpr int64_t kSpanMinRows = 6144;
 
 static inline size_t round_up_sz(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -68,10 +71,12 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = n
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
 }
 
-// Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp).
-template <typename T, int KIND, int NCB, int KMAX = kUpdKMax>
-static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
-                             hipStream_t st, hipEvent_t done) {
+// Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp): one launch over
+// the rows [0, m) of L and C and the columns [0, mc) of C (mc = m except for a launch that covers
+// only part of the rows of an LU update).
+template <typename T, int KIND, int NCB, int KMAX>
+static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t m, int64_t mc, int b, int skip, int slots,
+                              hipStream_t st, hipEvent_t done) {
   constexpr bool LOWER = (KIND == KIND_CHOL);
   constexpr int COLS = NCB * 16;
   auto kern = update_kernel<T, LOWER, NCB, KMAX>;
@@ -89,23 +94,49 @@ static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m
   a.C = C;
   a.ld = ld;
   a.m = (int)m;
+  a.mc = (int)mc;
   a.b = b;
   a.skip = skip;
   const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
   int64_t total_blocks = 0;
-  for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)m, LOWER, COLS);
+  for (int p = 0; p < npanels; ++p) total_blocks += update_blocks_of_panel(p, (int)mc, LOWER, COLS);
+  const double flops = (LOWER ? 1.0 : 2.0) * ((double)m * (double)mc - (double)skip * (double)skip) * (double)b;
+  if constexpr (LOWER) {
+    // a large trapezoid: work items of equal size that cross row panels (see update_span_kernel)
+    if (m >= kSpanMinRows && total_blocks >= 8 * (int64_t)slots) {
+      auto span = update_span_kernel<T, NCB, KMAX>;
+      static bool span_attr_done = false;
+      if (!span_attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(span), hipFuncAttributeMaxDynamicSharedMemorySize, LD::BYTES) !=
+            hipSuccess)
+          return DLA_ERR_HIP;
+        span_attr_done = true;
+      }
+      a.bpi = 1;
+      a.items = slots;
+      hipEvent_t p0 = nullptr, p1 = nullptr;
+      if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
+        hipExtLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, p0, p1, 0, a, total_blocks);
+        if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+        if (done && hipEventRecord(done, st) != hipSuccess) return DLA_ERR_HIP;
+        return DLA_SUCCESS;
+      }
+      if (done) hipExtLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, nullptr, done, 0, a, total_blocks);
+      else hipLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, a, total_blocks);
+      return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+    }
+  }
   // one 8-wave workgroup fits per compute unit: aim at one round of at most `slots` items
   a.bpi = (int)((total_blocks + slots - 1) / slots);
   if (a.bpi < 1) a.bpi = 1;
   int items = 0;
   for (;;) {
     items = 0;
-    for (int p = 0; p < npanels; ++p) items += update_items_of_panel(p, (int)m, a.bpi, LOWER, COLS);
+    for (int p = 0; p < npanels; ++p) items += update_items_of_panel(p, (int)mc, a.bpi, LOWER, COLS);
     if (items <= slots || a.bpi >= (1 << 20)) break;
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
   a.items = items;
-  const double flops = (LOWER ? 1.0 : 2.0) * ((double)m * (double)m - (double)skip * (double)skip) * (double)b;
   hipEvent_t p0 = nullptr, p1 = nullptr;
   if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
     // profiling: the dispatch carries the profiler's start / stop events, the completion event follows it
@@ -116,6 +147,37 @@ static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m
   }
   launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+}
+
+// All row panels of an LU update hold the same number of column blocks, so one launch cuts each into
+// the same number c of work items and uses c * panels of the `slots` compute units: 126 panels on
+// 224 units run at c = 1, on 56 % of the units.  Where that leaves more than a tenth of them idle, the
+// rows go in two launches, back to back, that each fill the units: the first floor(slots / (c + 1))
+// panels at c + 1 items per panel, the remaining few panels at as many items per panel as fit.
+template <typename T, int KIND, int NCB, int KMAX = kUpdKMax>
+static int launch_update_ncb(const T* L, const T* R, T* C, int64_t ld, int64_t m, int b, int skip, int slots,
+                             hipStream_t st, hipEvent_t done) {
+  if constexpr (KIND == KIND_LU) {
+    constexpr int COLS = NCB * 16;
+    const int npanels = (int)((m + kUpdRows - 1) / kUpdRows);
+    const int nblk = (int)((m + COLS - 1) / COLS);
+    const int c = npanels <= slots ? slots / npanels : 0;  // items per panel of the single launch
+    // (large updates only: the second launch costs a launch gap and a left-panel load per short work item)
+    if (m >= 4096 && c >= 1 && (int64_t)(c + 1) * 4 <= nblk && (int64_t)c * npanels * 10 < (int64_t)slots * 9) {
+      const int first = slots / (c + 1);                     // panels of the first launch
+      const int64_t rows_a = (int64_t)first * kUpdRows;
+      if (first >= 1 && rows_a < m && skip <= rows_a) {
+        int rc = launch_update_rows<T, KIND, NCB, KMAX>(L, R, C, ld, rows_a, m, b, skip, slots, st, nullptr);
+        if (rc != DLA_SUCCESS) return rc;
+        // at least four column blocks per work item in the second launch
+        const int64_t rest_blocks = (int64_t)(npanels - first) * nblk;
+        const int slots_b = rest_blocks / 4 < slots ? (int)(rest_blocks / 4) : slots;
+        return launch_update_rows<T, KIND, NCB, KMAX>(L + rows_a * ld, R, C + rows_a * ld, ld, m - rows_a, m, b, 0, slots_b,
+                                                      st, done);
+      }
+    }
+  }
+  return launch_update_rows<T, KIND, NCB, KMAX>(L, R, C, ld, m, m, b, skip, slots, st, done);
 }
 
 // fp32: 64-column blocks once every slot gets at least kWideMinBlocks of them (3-6 % faster at

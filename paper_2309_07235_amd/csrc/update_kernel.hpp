@@ -28,7 +28,11 @@
 // wave and iteration, right-operand bytes per iteration and the pipeline are the same as at depth 128
 // with NCB = 2.
 //
-// Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone.
+// Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone
+// (update_kernel).  One launch cuts every row panel into whole work items, which leaves compute units
+// idle when the panel count does not divide them well: an LU update is then given to two launches by
+// rows (host side), and a large lower-triangular update to update_span_kernel, whose work items are
+// equal runs of the column blocks of all panels and cross from one row panel into the next.
 #pragma once
 #include <type_traits>
 #include "dla_common.hpp"
@@ -48,9 +52,10 @@ template <typename T>
 struct UpdateArgs {
   const T* L;   // m x b left panel (L21)
   const T* R;   // LU: b x m right panel (U12);  Cholesky: the same m x b panel as L
-  T* C;         // m x m trailing matrix
+  T* C;         // m x mc trailing matrix
   int64_t ld;   // common leading dimension (all three live in the same matrix)
-  int m, b;
+  int m, b;     // rows of L and C; depth
+  int mc;       // columns of C and of R: m, except for an LU launch that covers only part of the rows
   int bpi;      // target number of column blocks per work item
   int items;    // number of work items = grid size
   int skip;     // the leading skip x skip block of C (skip: multiple of 16) is not written: another stream owns it
@@ -78,43 +83,21 @@ __host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool
   return (update_blocks_of_panel(p, m, lower, cols) + bpi - 1) / bpi;
 }
 
-template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax>
-__global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
-  static_assert(KMAX % 64 == 0 && kUpdThreads % KMAX == 0, "depth");
+// One segment of a work item: the row panel `panel` against the column blocks col_begin,
+// col_begin + col_step, ... whose first column lies below col_end.
+template <typename T, bool LOWER, int NCB, int KMAX>
+__device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const smem, const int panel, const int col_begin,
+                                               const int col_step, const int col_end) {
   using acc_t = typename Mfma<T>::acc_t;
   using LD = UpdateLds<T, LOWER, NCB, KMAX>;
   constexpr int kUpdCols = NCB * 16;  // columns per iteration
   constexpr int KSTEPS = KMAX / 4;    // 32 or 64
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  T* const smem = reinterpret_cast<T*>(smem_raw);
-
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, l4 = lane >> 4;
   const int m = g.m, b = g.b;
+  const int mc = LOWER ? g.m : g.mc;  // column extent (the lower-triangular form is always square)
   const int64_t ld = g.ld;
-
-  // ---- which work item: (row panel, first column, one-past-last column) ----------------------
-  const int npanels = (m + kUpdRows - 1) / kUpdRows;
-  int item = xcd_contiguous_id((int)blockIdx.x, g.items);
-  int panel = 0, cnt = 0;
-  for (;;) {
-    cnt = update_items_of_panel(panel, m, g.bpi, LOWER, kUpdCols);
-    if (item < cnt || panel + 1 >= npanels) break;
-    item -= cnt;
-    ++panel;
-  }
   const int row0 = panel * kUpdRows;
-  // The panel's column blocks are dealt round-robin to its items: item q takes blocks q, q + cnt,
-  // q + 2*cnt, ...  Items run side by side, so at any moment the items of one panel touch a run of
-  // adjacent 256-byte pieces of the same matrix rows (DRAM page locality), and every panel is at
-  // about the same right-operand block (L2 reuse).
-  const int nblocks = update_blocks_of_panel(panel, m, LOWER, kUpdCols);
-  const int width = LOWER ? ((panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m) : m;
-  const int col_begin = item * kUpdCols;         // first block of this item
-  const int col_step = cnt * kUpdCols;           // distance between its blocks
-  const int col_end = width;                     // a block is valid while its first column is < width
-  (void)nblocks;
-  if (col_begin >= col_end) return;  // uniform
 
   DLA_TRACE(0);
   // ---- left panel -> registers (through LDS for coalesced global reads) -----------------------
@@ -163,7 +146,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
     if (!LOWER) {
       const int k = tid / TPK, c0 = (tid % TPK) * BPT;
       const T* p = g.R + (int64_t)(k < b ? k : b - 1) * ld;
-      const bool full = (j0 + kUpdCols <= m) && (k < b);
+      const bool full = (j0 + kUpdCols <= mc) && (k < b);
       if (full) {
 #pragma unroll
         for (int i = 0; i < BPT; ++i) bst[i] = p[j0 + c0 + i];
@@ -171,8 +154,8 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
           const int c = j0 + c0 + i;
-          const T x = p[c < m ? c : m - 1];
-          bst[i] = (k < b && c < m) ? x : T(0);
+          const T x = p[c < mc ? c : mc - 1];
+          bst[i] = (k < b && c < mc) ? x : T(0);
         }
       }
     } else {
@@ -216,7 +199,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
     for (int q = 0; q < NCB; ++q) c[q] = acc_t{0, 0, 0, 0};
     return;
 #endif
-    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
+    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
     if (full) {
 #pragma unroll
       for (int q = 0; q < NCB; ++q)
@@ -229,8 +212,8 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
         for (int v = 0; v < 4; ++v) {
           const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
           const int rc = (wrow0 + r < m) ? r : m - 1 - wrow0;  // row index stays inside the matrix
-          const T x = Cw[(int64_t)rc * ld + (cc < m ? cc : m - 1)];
-          c[q][v] = (wrow0 + r < m && cc < m) ? x : T(0);
+          const T x = Cw[(int64_t)rc * ld + (cc < mc ? cc : mc - 1)];
+          c[q][v] = (wrow0 + r < m && cc < mc) ? x : T(0);
         }
     }
   };
@@ -238,14 +221,14 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
 #ifdef DLA_UPD_NO_STORE  // development switch: keep one store per wave so the work is not optimised away
     if (j0 != col_begin) return;
 #endif
-    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= m);
+    const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
 #pragma unroll
     for (int q = 0; q < NCB; ++q) {
       if (wrow0 < g.skip && j0 + q * 16 < g.skip) continue;  // uniform per wave: the excluded leading block
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int r = Mfma<T>::row_of(v, lane), cc = j0 + q * 16 + l15;
-        if (full || (wrow0 + r < m && cc < m)) Cw[(int64_t)r * ld + cc] = c[q][v];
+        if (full || (wrow0 + r < m && cc < mc)) Cw[(int64_t)r * ld + cc] = c[q][v];
       }
     }
   };
@@ -343,6 +326,73 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
       if (grp == 1) store_c(c2, jp);
       break;
     }
+  }
+}
+
+template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax>
+__global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
+  static_assert(KMAX % 64 == 0 && kUpdThreads % KMAX == 0, "depth");
+  constexpr int kUpdCols = NCB * 16;  // columns per iteration
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  T* const smem = reinterpret_cast<T*>(smem_raw);
+  const int m = g.m;
+  const int mc = LOWER ? g.m : g.mc;  // column extent (the lower-triangular form is always square)
+
+  // ---- which work item: (row panel, first column, one-past-last column) ----------------------
+  const int npanels = (m + kUpdRows - 1) / kUpdRows;
+  int item = xcd_contiguous_id((int)blockIdx.x, g.items);
+  int panel = 0, cnt = 0;
+  for (;;) {
+    cnt = update_items_of_panel(panel, LOWER ? m : mc, g.bpi, LOWER, kUpdCols);
+    if (item < cnt || panel + 1 >= npanels) break;
+    item -= cnt;
+    ++panel;
+  }
+  // The panel's column blocks are dealt round-robin to its items: item q takes blocks q, q + cnt,
+  // q + 2*cnt, ...  Items run side by side, so at any moment the items of one panel touch a run of
+  // adjacent 256-byte pieces of the same matrix rows (DRAM page locality), and every panel is at
+  // about the same right-operand block (L2 reuse).
+  const int nblocks = update_blocks_of_panel(panel, LOWER ? m : mc, LOWER, kUpdCols);
+  const int width = LOWER ? ((panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m) : mc;
+  const int col_begin = item * kUpdCols;         // first block of this item
+  const int col_step = cnt * kUpdCols;           // distance between its blocks
+  const int col_end = width;                     // a block is valid while its first column is < width
+  (void)nblocks;
+  if (col_begin >= col_end) return;  // uniform
+
+  update_segment<T, LOWER, NCB, KMAX>(g, smem, panel, col_begin, col_step, col_end);
+}
+
+// The same update with work items of exactly equal size for the lower-triangular form, whose row
+// panels hold 1 .. m/128 times as many column blocks: the column blocks of all panels, panel after
+// panel, are cut into gridDim.x equal runs, and a workgroup walks its run, reloading the left panel
+// where the run crosses into the next row panel.  (Per-panel items, as above, leave a quarter of the
+// compute units idle on a large trapezoid: a small panel's item is a fraction of a large panel's.)
+template <typename T, int NCB, int KMAX = kUpdKMax>
+__global__ void __launch_bounds__(kUpdThreads) update_span_kernel(const UpdateArgs<T> g, const int64_t total_blocks) {
+  constexpr int kUpdCols = NCB * 16;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  T* const smem = reinterpret_cast<T*>(smem_raw);
+  const int m = g.m;
+  const int npanels = (m + kUpdRows - 1) / kUpdRows;
+  const int item = xcd_contiguous_id((int)blockIdx.x, (int)gridDim.x);
+  int64_t lo = ((int64_t)item * total_blocks) / (int64_t)gridDim.x;
+  int64_t left = ((int64_t)(item + 1) * total_blocks) / (int64_t)gridDim.x - lo;  // blocks of this item
+  int panel = 0;
+  while (panel + 1 < npanels && lo >= update_blocks_of_panel(panel, m, true, kUpdCols)) {
+    lo -= update_blocks_of_panel(panel, m, true, kUpdCols);
+    ++panel;
+  }
+  while (left > 0 && panel < npanels) {  // uniform over the workgroup
+    const int here = update_blocks_of_panel(panel, m, true, kUpdCols);
+    const int64_t take = left < here - lo ? left : here - lo;
+    const int width = (panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m;
+    const int end = (int)(lo + take) * kUpdCols;
+    update_segment<T, true, NCB, KMAX>(g, smem, panel, (int)lo * kUpdCols, kUpdCols, end < width ? end : width);
+    lds_barrier();  // the next segment restages the left panel through the same memory
+    left -= take;
+    lo = 0;
+    ++panel;
   }
 }
 

@@ -374,7 +374,8 @@ def test_n8192_fp32_properties(B, oracle):
 
 
 @pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96),
-                                 (300, 256), (1000, 200), (777, 144)])  # depth above 128: the two-panel form
+                                 (300, 256), (1000, 200), (777, 144),   # depth above 128: the two-panel form
+                                 (6200, 256), (6333, 128)])  # large: row-split launches (LU), panel-crossing items (Cholesky)
 @pytest.mark.parametrize("lower", [False, True])
 def test_rank_update_alone(B, oracle, m, k, lower):
     """dla_rank_update (the bulk trailing update on its own) against the oracle's plain product (the E of a
