@@ -59,10 +59,16 @@ __device__ inline void lds_barrier() {
 // kernels of one process cannot run side by side (a profiler or debugger that serialises them):
 // the consumer that gives up sets *broken, every later wait returns at once, and the pipeline's
 // last kernel reports it.  Data computed after that is not valid.
+// The device-scope release and acquire are each done by ONE thread: they write back and invalidate
+// caches that all waves of the workgroup share, and the workgroup barrier next to them orders the
+// other waves' stores before the release and their loads after the acquire.  (Issued by every wave,
+// the same fences take about a microsecond longer per hand-over.)
 __device__ inline void chain_signal(int* counter, int add, int tid) {
-  __threadfence();   // this thread's global stores, device scope
-  __syncthreads();   // every thread of the workgroup has fenced
-  if (tid == 0) __hip_atomic_fetch_add(counter, add, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();   // every wave's global stores have been performed for the workgroup
+  if (tid == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 }
 __device__ inline void chain_wait(const int* counter, int target, int* broken, int tid) {
   if (tid == 0) {
@@ -75,9 +81,9 @@ __device__ inline void chain_wait(const int* counter, int target, int* broken, i
       }
     }
     if (!ok) __hip_atomic_store(broken, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // loads below see what the producer published
   }
   __syncthreads();
-  __threadfence();   // acquire: loads below see what the producer published
 }
 
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator complex dies, workgroups are dealt round-robin
