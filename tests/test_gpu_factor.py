@@ -322,6 +322,30 @@ def test_repeated_calls_are_bitwise_identical(B):
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("kind,n", [("lu", 2100), ("chol", 2100), ("lu", 4000)])
+def test_forty_calls_in_a_row_give_the_same_bits(B, kind, n):
+    """The kernels of the latency chain hand their results over through memory while both still run; a
+    hand-over that let a consumer read stale data would show as a run that differs.  Forty factorisations of
+    one matrix, enqueued without synchronisation in between, compared on the device with the first."""
+    import torch
+    announce(f"forty calls {kind} n={n}")
+    H = inputs.diag_dominant_matrix(n, 46) if kind == "lu" else inputs.spd_matrix(n, 46)
+    src = to_device(H)
+    fn = B.lu_factor if kind == "lu" else B.cholesky_factor
+    ws = torch.empty(B.factor_workspace_bytes(n, B.DLA_F64, None), dtype=torch.uint8, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    first = src.clone()
+    fn(first, None, workspace=ws, info=info)
+    work = torch.empty_like(src)
+    differing = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for _ in range(40):
+        work.copy_(src)
+        fn(work, None, workspace=ws, info=info)
+        differing += (work != first).sum()
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0 and int(differing.item()) == 0
+
+
 # ------------------------------------------------------------------ fp32 variant
 @pytest.mark.parametrize("n,nb", [(500, 128), (1000, 64)])
 def test_fp32_factorisations(B, oracle, n, nb):
