@@ -75,8 +75,8 @@ typedef struct {
 
 /*
  * Schedule of a blocked right-looking factorisation.  nb is the panel width
- * (block size), update the schedule of the trailing-matrix (Schur complement)
- * update that dominates the run time: all fields 0 (the default) selects the
+ * (block size), update the schedule of the trailing-matrix update
+ * A22 -= L21 * U12 (lower(A22) -= L21 * L21^T for Cholesky) that dominates the run time: all fields 0 (the default) selects the
  * library's panel-stationary rank-nb update kernel, anything else runs the
  * update as tiled GEMMs with that schedule, so that a search can drive it.
  */
@@ -126,8 +126,8 @@ int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_f
                     void* d_workspace, size_t workspace_bytes, void* hip_stream, int* d_info);
 
 /*
- * Solving A*X = B with the factors (same Section: both decompositions are introduced as the way
- * to solve systems of linear equations).  lu_solve: L*Y = B by forward substitution (unit diagonal),
+ * Solving A*X = B with the factors (paper, Section "Introduction": LU and Cholesky are named as the
+ * factorisations behind solving systems of linear equations).  lu_solve: L*Y = B by forward substitution (unit diagonal),
  * then U*X = Y backward.  cholesky_solve: L*Y = B, then L^T*X = Y (only the lower triangle is read).
  *   d_lu / d_l   device, n x n, leading dimension lda: the output of lu_factor / cholesky_factor;
  *                read only.
@@ -187,8 +187,9 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
              void* hip_stream);
 
 /*
- * The default trailing update of the factorisations on its own (paper, Section "Linear Algebra
- * Benchmarks": the Schur-complement step), exported so that it can be timed and tested in isolation:
+ * The default trailing update of the factorisations on its own (a step of the blocked algorithm that
+ * computes the decompositions of the paper's Section "Linear Algebra Benchmarks"; the paper itself does
+ * not describe a blocking), exported so that it can be timed and tested in isolation:
  *   lower == 0:  C -= L*R          L m x k, R k x m, C m x m            (LU)
  *   lower == 1:  lower(C) -= L*L^T in blocks of 128 rows: row block i is updated in columns
  *                0 .. 128*(i+1)-1, so the part of diagonal blocks above the diagonal changes too;

@@ -250,7 +250,7 @@ void oracle_symv_lower(const double *a, int64_t ld, int64_t n, const double *x, 
 
 /*
  * Solving A*X = B with the factors (the use the paper names for both
- * decompositions, Section "Linear Algebra Benchmarks": systems of linear
+ * decompositions, Section "Introduction": solving systems of linear
  * equations).  B is n x nrhs, row-major, overwritten by X; every column is an
  * independent system, so the column loop carries the OpenMP pragma and each
  * column's sums are added in a fixed order.

@@ -2,8 +2,9 @@
 // the trailing matrix the NEXT diagonal block waits for is
 //     A[k+1][k+1] -= (A[k+1][k] * R^-1) * (L11^-1 * A[k][k+1])          (LU,  R = U11)
 //     A[k+1][k+1] -= (A[k+1][k] * L11^-T) * (A[k+1][k] * L11^-T)^T      (Cholesky)
-// This kernel computes exactly that b x b piece (paper, Section "Linear Algebra Benchmarks": the
-// Schur-complement step of the two factorisations) straight from the un-solved panel heads, so the
+// This kernel computes exactly that b x b piece (a step of the blocked form of the decompositions
+// A = L*U and A = L*L^T of the paper's Section "Linear Algebra Benchmarks"; the blocking is this
+// library's, not the paper's) straight from the un-solved panel heads, so the
 // next diagonal block can be factored while the full panel solves and the rest of the update run
 // on other streams.  The panel heads are only read, and may be given as copies, so the panel solve
 // that overwrites them in the matrix need not wait for this kernel.

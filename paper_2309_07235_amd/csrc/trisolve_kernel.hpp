@@ -1,5 +1,5 @@
-// Solving with the factors (paper, Section "Linear Algebra Benchmarks": both decompositions are
-// introduced as the way to solve systems of linear equations):  A X = B  becomes  L Y = B, U X = Y
+// Solving with the factors (paper, Section "Introduction": LU and Cholesky are named as the
+// factorisations behind solving systems of linear equations):  A X = B  becomes  L Y = B, U X = Y
 // after lu_factor and  L Y = B, L^T X = Y  after cholesky_factor.  The host driver walks the
 // triangular matrix in blocks of up to 128 rows.  The blocks' own triangular systems are taken off
 // the chain of the substitution by inverting every diagonal block up front (this kernel: one

@@ -3,7 +3,7 @@
 The paper tunes its kernels with an iterative loop (Section "Proposed Autotuning Framework", steps 1-5):
 a search method proposes a parameter configuration, the kernel is built and run with it, the measured
 runtime goes back to the search and into a performance database, until a budget of n evaluations is
-spent; the best entry of the database is the result.  Its search method (Section "Background", ytopt)
+spent; the best entry of the database is the result.  Its search method (Section "Backgrounds", ytopt)
 is Bayesian optimisation with a Random-Forest surrogate and the lower-confidence-bound acquisition
 function; its baseline is random enumeration.
 

@@ -21,3 +21,9 @@ def to_host(t) -> np.ndarray:
     import torch
     torch.cuda.synchronize()
     return t.detach().cpu().numpy()
+
+
+def oracle_product(oracle, X, Y) -> np.ndarray:
+    """X * Y by the oracle's plain triple loop: the E of a 3mm whose second product is empty-sized."""
+    X, Y = np.ascontiguousarray(X), np.ascontiguousarray(Y)
+    return oracle.mm3(X, Y, np.zeros((Y.shape[1], 1)), np.zeros((1, 1)), return_intermediates=True)[1]

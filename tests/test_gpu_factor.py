@@ -8,12 +8,12 @@ import numpy as np
 import pytest
 
 from paper_2309_07235_amd import inputs
-from tests.gpu_util import announce, to_device, to_host
-from tests.metrics import EPS32, EPS64, max_rel_err
+from tests.gpu_util import announce, oracle_product, to_device, to_host
+from tests.metrics import EPS32, EPS64, cholesky_rel_err, lu_rel_err, max_rel_err
 
 pytestmark = pytest.mark.gpu
 
-TOL64 = 1e-9   # max relative error, denominator floored at the RMS of the expected factor entries
+TOL64 = 1e-9   # max relative error; L, strict upper U and the diagonal each floored at their own RMS (tests/metrics.py)
 TOL32 = 1e-4
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked.json")
 
@@ -52,7 +52,7 @@ def _gpu_chol(B, A, params=None, dtype=None, want_info=True):
 def _check_lu(oracle, got, A, n, tol=TOL64, eps=EPS64):
     want, info = oracle.lu(A)
     assert info == 0
-    assert max_rel_err(got, want) <= tol
+    assert lu_rel_err(got, want) <= tol
     assert oracle.lu_residual(A, got) <= 10 * max(n, 1) * eps
 
 
@@ -60,7 +60,7 @@ def _check_chol(oracle, got, A, n, tol=TOL64, eps=EPS64):
     want, info = oracle.cholesky(A)
     assert info == 0
     low = np.tril(np.ones((n, n), dtype=bool))
-    assert max_rel_err(got[low], want[low]) <= tol
+    assert cholesky_rel_err(got, want) <= tol
     assert np.all(got[~low] == 0.0), "strict upper triangle must be exactly zero"
     assert oracle.cholesky_residual(A, got) <= 10 * max(n, 1) * eps
 
@@ -188,7 +188,7 @@ def test_n8192_properties(B, oracle):
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS64 * np.linalg.norm(y0)
     announce("N=8192 LU sampled rows against the oracle's full factorisation")
     want, _ = oracle.lu(A)
-    assert max_rel_err(lu, want) <= TOL64
+    assert lu_rel_err(lu, want) <= TOL64
     del want, lu
     announce("N=8192 Cholesky reconstruction")
     A[np.diag_indices(n)] += 1.0 - float(n)  # same Gram matrix, +I instead of +N*I: the SPD generator
@@ -202,7 +202,7 @@ def test_n8192_properties(B, oracle):
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS64 * np.linalg.norm(y0)
     announce("N=8192 Cholesky against the oracle's full factorisation")
     want, _ = oracle.cholesky(A)
-    assert max_rel_err(L, want) <= TOL64
+    assert cholesky_rel_err(L, want) <= TOL64
 
 
 @pytest.mark.parametrize("kind,n", [("lu", 5000), ("lu", 3500), ("chol", 6100), ("chol", 4700)])
@@ -364,8 +364,9 @@ def test_fp32_factorisations(B, oracle, n, nb):
 
 def test_n8192_fp32_properties(B, oracle):
     """The fp32 variant at N=8192, block size 128: exact all-ones factors of the min-index matrix (every
-    intermediate is an integer below 2^24), and randomised reconstruction checks of the seeded inputs rounded to
-    fp32, with the oracle's fp64 matrix-vector routines applied to the fp32 data."""
+    intermediate is an integer below 2^24); for the seeded inputs rounded to fp32, randomised reconstruction
+    checks with the oracle's fp64 matrix-vector routines, and the factors element by element against the
+    fp64 oracle's factorisation of the same fp32-rounded matrix."""
     import torch
     n = 8192
     announce("fp32 N=8192 min-index exact")
@@ -384,7 +385,10 @@ def test_n8192_fp32_properties(B, oracle):
         x = inputs.uniform_matrix(6, 70 + t, n, 1).ravel()
         y0, y1 = oracle.matvec(A64, x), oracle.lu_apply(lu64, x)
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS32 * np.linalg.norm(y0)
-    del lu, lu64
+    announce("fp32 N=8192 LU element by element against the fp64 oracle on the fp32-rounded input")
+    want, winfo = oracle.lu(A64)
+    assert winfo == 0 and lu_rel_err(lu64, want) <= TOL32
+    del lu, lu64, want
     announce("fp32 N=8192 Cholesky reconstruction")
     A64[np.diag_indices(n)] += 1.0 - float(n)  # the SPD generator: same Gram matrix, +I
     S32 = A64.astype(np.float32)
@@ -395,6 +399,9 @@ def test_n8192_fp32_properties(B, oracle):
         x = inputs.uniform_matrix(6, 80 + t, n, 1).ravel()
         y0, y1 = oracle.symv_lower(S64, x), oracle.cholesky_apply(L64, x)
         assert np.linalg.norm(y0 - y1) <= 10 * n * EPS32 * np.linalg.norm(y0)
+    announce("fp32 N=8192 Cholesky element by element against the fp64 oracle on the fp32-rounded input")
+    want, winfo = oracle.cholesky(S64)
+    assert winfo == 0 and cholesky_rel_err(L64, want) <= TOL32
 
 
 @pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96),
@@ -415,7 +422,7 @@ def test_rank_update_alone(B, oracle, m, k, lower):
     got = to_host(a)
     exp = A.copy()
     def product(X, Y):
-        return oracle.mm3(X, Y, np.zeros((Y.shape[1], 1)), np.zeros((1, 1)), return_intermediates=True)[1]
+        return oracle_product(oracle, X, Y)
 
     if lower:
         full = A[k:, k:] - product(A[k:, :k], np.ascontiguousarray(A[k:, :k].T))

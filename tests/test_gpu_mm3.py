@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2309_07235_amd import inputs
-from tests.gpu_util import announce, to_device, to_host
+from tests.gpu_util import announce, oracle_product, to_device, to_host
 from tests.metrics import EPS32, EPS64, fro_rel_err, max_rel_err
 
 pytestmark = pytest.mark.gpu
@@ -172,24 +172,20 @@ def test_strided_operands_and_stream(B, oracle):
 
 
 @pytest.mark.parametrize("op", [0, 1, 2, 3])
-def test_gemm_building_block(B, op):
-    """dla_gemm: assign, subtract, and the lower-triangular A*B^T update, against numpy."""
+def test_gemm_building_block(B, oracle, op):
+    """dla_gemm: assign, subtract, and the lower-triangular A*B^T update, against the oracle's plain product."""
     import torch
     announce(f"dla_gemm op={op}")
     m, n, k = (203, 203, 77) if op == 2 else (203, 157, 77)
     a = inputs.uniform_matrix(20, 0, m, k)
     b = inputs.uniform_matrix(20, 1, n, k) if op >= 2 else inputs.uniform_matrix(20, 1, k, n)
     c0 = inputs.uniform_matrix(20, 2, m, n)
+    ab = oracle_product(oracle, a, b.T if op >= 2 else b)
     for tile in ((128, 128), (64, 64), (16, 16)):
         c = to_device(c0)
         B.dla_gemm(op, to_device(a), to_device(b), c, B.GemmParams(tile[0], tile[1], 0, 0, 0, 0))
         got = to_host(c)
-        if op == 0:
-            want = a @ b
-        elif op == 1:
-            want = c0 - a @ b
-        else:
-            want = c0 - a @ b.T  # op 2: lower tiles only, op 3: everywhere
+        want = ab if op == 0 else c0 - ab  # op 2: lower tiles only, op 3: everywhere
         if op == 2:
             low = np.tril(np.ones((m, n), dtype=bool))
             assert max_rel_err(got[low], want[low]) <= TOL64
