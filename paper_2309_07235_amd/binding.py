@@ -12,10 +12,7 @@ import ctypes
 from pathlib import Path
 
 _HERE = Path(__file__).resolve().parent
-import os as _os
-
-# DLA_LIB overrides the library path (development: A/B runs of two builds)
-LIB_PATH = Path(_os.environ["DLA_LIB"]) if _os.environ.get("DLA_LIB") else _HERE / "libdla_mi355x.so"
+LIB_PATH = _HERE / "libdla_mi355x.so"
 
 DLA_F64, DLA_F32 = 0, 1
 DLA_SUCCESS, DLA_ERR_UNSUPPORTED_PARAMS, DLA_ERR_WORKSPACE, DLA_ERR_HIP, DLA_ERR_TOO_LARGE = 0, 1, 2, 3, 4

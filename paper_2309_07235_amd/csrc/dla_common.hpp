@@ -55,10 +55,11 @@ __device__ inline void lds_barrier() {
 // threads make their stores visible device-wide and one of them bumps a counter; the consumer polls
 // the counter with one thread before it touches the data.  The consumer is launched early only to
 // hide its launch latency; the streams are arranged so that the producer never depends on the
-// consumer.  The poll is bounded (about a tenth of a second), so that every wave exits even where
-// kernels of one process cannot run side by side (a profiler or debugger that serialises them):
-// the consumer that gives up sets *broken, every later wait returns at once, and the pipeline's
-// last kernel reports it.  Data computed after that is not valid.
+// consumer.  The poll is bounded by the constant-rate wall clock (budget_ticks of it, sized on the
+// host from the longest kernel the producer may be queued behind), so that every wave exits even
+// where kernels of one process cannot run side by side (a profiler or debugger that serialises
+// them): the consumer that gives up sets *broken, every later wait returns at once, and the
+// pipeline's last kernel reports it.  Data computed after that is not valid.
 // The device-scope release and acquire are each done by ONE thread: they write back and invalidate
 // caches that all waves of the workgroup share, and the workgroup barrier next to them orders the
 // other waves' stores before the release and their loads after the acquire.  (Issued by every wave,
@@ -70,14 +71,18 @@ __device__ inline void chain_signal(int* counter, int add, int tid) {
     __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
-__device__ inline void chain_wait(const int* counter, int target, int* broken, int tid) {
+__device__ inline void chain_wait(const int* counter, int target, int* broken, long long budget_ticks, int tid) {
   if (tid == 0) {
-    bool ok = false;
-    for (int spins = 0; spins < (1 << 16) && !ok; ++spins) {
-      ok = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
-      if (!ok) {
-        if ((spins & 63) == 63 && __hip_atomic_load(broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+    bool ok = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
+    if (!ok) {
+      const long long t0 = wall_clock64();
+      for (int spins = 0; !ok && spins < (1 << 24); ++spins) {  // the spin cap is a second, absolute bound
         __builtin_amdgcn_s_sleep(16);
+        ok = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
+        if (!ok && (spins & 63) == 63) {
+          if (__hip_atomic_load(broken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+          if (wall_clock64() - t0 > budget_ticks) break;
+        }
       }
     }
     if (!ok) __hip_atomic_store(broken, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

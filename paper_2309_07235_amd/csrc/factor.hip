@@ -59,13 +59,8 @@ static inline void launch_ev(K kern, dim3 grid, dim3 block, int lds, hipStream_t
 template <typename T, int KIND>
 static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = nullptr) {
   auto kern = diag_kernel<T, KIND>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            diag_lds_bytes<T>()) != hipSuccess)
-      return DLA_ERR_HIP;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), diag_lds_bytes<T>())) return DLA_ERR_HIP;
   ProfileScope scope(PHASE_DIAG, 0.0, st);
   launch_ev(kern, dim3(1), dim3(kDiagThreads), diag_lds_bytes<T>(), st, done, a);
   return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
@@ -81,13 +76,8 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
   constexpr int COLS = NCB * 16;
   auto kern = update_kernel<T, LOWER, NCB, KMAX>;
   using LD = UpdateLds<T, LOWER, NCB, KMAX>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            LD::BYTES) != hipSuccess)
-      return DLA_ERR_HIP;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), LD::BYTES)) return DLA_ERR_HIP;
   UpdateArgs<T> a;
   a.L = L;
   a.R = R;
@@ -105,13 +95,8 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
     // a large trapezoid: work items of equal size that cross row panels (see update_span_kernel)
     if (m >= kSpanMinRows && total_blocks >= 8 * (int64_t)slots) {
       auto span = update_span_kernel<T, NCB, KMAX>;
-      static bool span_attr_done = false;
-      if (!span_attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(span), hipFuncAttributeMaxDynamicSharedMemorySize, LD::BYTES) !=
-            hipSuccess)
-          return DLA_ERR_HIP;
-        span_attr_done = true;
-      }
+      static LdsLimitOnce span_lds_limit;
+      if (!span_lds_limit.ensure(reinterpret_cast<const void*>(span), LD::BYTES)) return DLA_ERR_HIP;
       a.bpi = 1;
       a.items = slots;
       hipEvent_t p0 = nullptr, p1 = nullptr;
@@ -208,13 +193,8 @@ template <typename T, int KIND>
 static int launch_solve(SolveArgs<T> sa, hipStream_t st, hipEvent_t done = nullptr) {
   if (sa.b % kIb != 0) return DLA_ERR_UNSUPPORTED_PARAMS;  // a panel with something behind it is always nb wide
   auto kern = solve_kernel<T, KIND>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            solve_lds_bytes<T>()) != hipSuccess)
-      return DLA_ERR_HIP;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), solve_lds_bytes<T>())) return DLA_ERR_HIP;
   const int per_wg = (kSolveThreads / 64) * kIb;  // panel rows/columns one workgroup solves
   const int wgs = (sa.m + per_wg - 1) / per_wg;
   sa.n_top = (KIND == KIND_LU) ? wgs : 0;
@@ -229,13 +209,8 @@ template <typename T, int KIND>
 static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done, int* workgroups) {
   auto kern = head_kernel<T, KIND>;
   constexpr int lds = head_lds_bytes<T, KIND>();
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
-        hipSuccess)
-      return DLA_ERR_HIP;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), lds)) return DLA_ERR_HIP;
   const int nt = (a.bn + kHeadTile - 1) / kHeadTile;
   const int grid = (KIND == KIND_LU) ? nt * nt : nt * (nt + 1) / 2;
   *workgroups = grid;
@@ -251,6 +226,7 @@ struct LookaheadCtx {
   hipStream_t panel = nullptr;  // panel solves + strip updates
   hipStream_t bulk = nullptr;   // bulk trailing updates
   hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  double ticks_per_s = 1e8;     // rate of the constant wall clock the in-kernel waits are bounded by
   bool ok = false;
 };
 static LookaheadCtx& lookahead_ctx() {
@@ -260,6 +236,10 @@ static LookaheadCtx& lookahead_ctx() {
                 hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; i < 8 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
+    int dev = 0, khz = 0;
+    if (good && hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+      ctx.ticks_per_s = 1e3 * (double)khz;
     ctx.ok = good;
   }
   return ctx;
@@ -286,7 +266,9 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   if (rc != DLA_SUCCESS) return rc;
   if (n == 0) return DLA_SUCCESS;
   if (!ws || ws_bytes < factor_workspace_bytes_impl(n, dt, p) || ((uintptr_t)ws % 256)) return DLA_ERR_WORKSPACE;
-  const bool auto_tile = !(p && (p->update.tile_m != 0 || p->update.tile_n != 0));
+  // the panel-stationary update kernel unless the caller names any field of a tiled schedule
+  const bool auto_tile = !(p && (p->update.tile_m != 0 || p->update.tile_n != 0 || p->update.tile_k != 0 ||
+                                 p->update.unroll_k != 0 || p->update.wave_m != 0 || p->update.wave_n != 0));
 
   unsigned char* wsb = static_cast<unsigned char*>(ws);
   const size_t set = inv_set_bytes(dt);
@@ -303,6 +285,9 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   int* const chain = reinterpret_cast<int*>(wsb + 4 * set + 4 * head_copy_bytes(dt));
   bool chained = false;  // set by the look-ahead path
   int heads_done = 0;    // head workgroups launched so far = what the next diagonal block waits for
+  // A kernel of the chain may sit behind the largest bulk update of the call: its wait lasts at most a
+  // tenth of a second plus eight times that update's duration at a tenth of the matrix-pipe peak.
+  long long wait_ticks = 0;  // set with the pipeline's context
   auto diag = [&](int64_t k0, int step, hipStream_t s, hipEvent_t done) -> int {
     DiagArgs<T> da;
     da.A = A + k0 * lda + k0;
@@ -316,6 +301,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     da.wait_target = heads_done;
     da.done_counter = chained ? chain : nullptr;
     da.broken = chained ? chain + 2 : nullptr;
+    da.wait_ticks = wait_ticks;
     return launch_diag<T, KIND>(da, s, done);
   };
   // panel solves of the block column / block row behind diagonal block k0
@@ -427,6 +413,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     std::lock_guard<std::mutex> submit_lock(submit_mutex);
     LookaheadCtx& ctx = lookahead_ctx();
     if (!ctx.ok) return DLA_ERR_HIP;
+    wait_ticks = (long long)(ctx.ticks_per_s * (0.1 + 8.0 * (2.0 * (double)n * (double)n * 2.0 * nb) / 8e12));
     hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_bulk = ctx.ev[2], e_start = ctx.ev[3], e_strip = ctx.ev[6];
     hipEvent_t e_diag[2] = {ctx.ev[4], ctx.ev[5]};  // by step parity
     constexpr int SOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT;
@@ -567,6 +554,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       ha.wait_target = step + 1;
       ha.done_counter = chained ? chain + 1 : nullptr;
       ha.broken = chain + 2;
+      ha.wait_ticks = wait_ticks;
       int head_wgs = 0, r;
       if ((r = launch_head<T, KIND>(ha, ctx.head, e_head, &head_wgs)) != DLA_SUCCESS) return r;
       heads_done += head_wgs;
@@ -575,7 +563,8 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       return DLA_SUCCESS;
     };
 
-    chained = lookahead == 1;
+    // a wait that gives up can only be reported through d_info: without it the chain is ordered by events
+    chained = lookahead == 1 && d_info != nullptr;
     // A call starts behind the previous pipelined call of the process: its first kernels would
     // otherwise wait in place for work that is queued behind that call on the helper streams.
     hipEvent_t e_call_done = ctx.ev[7];
@@ -641,6 +630,7 @@ int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info) {
   da.wait_target = 1;  // nobody will ever count to one
   da.done_counter = chain;
   da.broken = chain + 2;
+  da.wait_ticks = 5000000;  // 0.05 s at the usual 100 MHz
   return launch_diag<double, KIND_LU>(da, st, nullptr);
 }
 

@@ -14,11 +14,6 @@
 #include <type_traits>
 #include "dla_common.hpp"
 
-// Optional phase tracing for development harnesses; expands to nothing in the library build.
-#ifndef DLA_TRACE
-#define DLA_TRACE(i)
-#endif
-
 namespace dla {
 
 constexpr int kNbMax = 128;            // largest block size
@@ -258,6 +253,7 @@ struct DiagArgs {
   int wait_target;
   int* done_counter;
   int* broken;   // set by a wait that gave up (see chain_wait); reported as info = -1
+  long long wait_ticks;  // how long a wait may last, in ticks of the constant-rate wall clock
 };
 
 template <typename T, int KIND>
@@ -274,8 +270,7 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
   const int nblk = (b + kIb - 1) / kIb;
   const int bp = nblk * kIb;  // padded size: rows/columns b..bp-1 are identity
 
-  DLA_TRACE(0);
-  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, tid);
+  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, g.wait_ticks, tid);
   if (tid == 0) s_info = 0;
   // ---- load, padding with the identity: thread = two adjacent columns, 8 rows per pass, all
   // loads issued before the first LDS store
@@ -347,7 +342,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
     for (int v = 0; v < 4; ++v) S[(c0 + Mfma<T>::row_of(v, lane)) * kSld + d0 + l15] = acc[v];
   };
 
-  DLA_TRACE(1);
   // two independent blocks at once
   auto update_block2 = [&](int o, int c0, int d0, int c1, int d1) {
     typename Mfma<T>::acc_t acc0, acc1;
@@ -378,7 +372,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
 
   if (wave == 0) factor_sub_block(0);
   __syncthreads();
-  DLA_TRACE(2);
 
   for (int r = 0; r + 1 < nblk; ++r) {
     const int o = r * kIb;
@@ -430,7 +423,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
       for (int j = 0; j < 16; ++j) S[row * kSld + o + j] = x[j];
     }
     __syncthreads();
-    DLA_TRACE(3 + 2 * r);
     // ---- inner trailing update on MFMA.  Wave 0 updates the next diagonal sub-block first and
     // factors it while the other waves update the remaining blocks (look-ahead inside the block).
     const int nrem = rem / kIb;
@@ -451,7 +443,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
       }
     }
     __syncthreads();
-    DLA_TRACE(4 + 2 * r);
   }
 
   // ---- inverses of the diagonal sub-blocks: one 16-lane row per sub-block ---------------------
@@ -484,7 +475,6 @@ __global__ void __launch_bounds__(kDiagThreads) diag_kernel(const DiagArgs<T> g)
       if (c + 1 < b) p[1] = (KIND == KIND_LU || c + 1 <= r) ? S[r * kSld + c + 1] : T(0);
     }
   }
-  DLA_TRACE(20);
   if (tid == 0 && g.info) {
     if (g.k0 == 0) *g.info = s_info;  // first block of the call: initialise
     else if (s_info != 0 && *g.info == 0) *g.info = s_info;

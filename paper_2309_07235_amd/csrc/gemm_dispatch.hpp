@@ -3,6 +3,7 @@
 // by the build script) so the menu builds in parallel.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include "gemm_kernel.hpp"
 
 namespace dla {
@@ -12,6 +13,17 @@ struct GemmSchedule {
 };
 
 constexpr int kMaxLdsBytes = 160 * 1024;  // LDS per CU on gfx950
+
+// Raises a kernel's dynamic-LDS limit once per process (one static instance per kernel instantiation).
+// First calls may come from several host threads at the same time.
+struct LdsLimitOnce {
+  std::once_flag flag;
+  hipError_t err = hipSuccess;
+  bool ensure(const void* kernel, int bytes) {
+    std::call_once(flag, [&] { err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+    return err == hipSuccess;
+  }
+};
 
 // The macro-tile menu: X(TM, TN, WM, WN).  The first entry with a given
 // (TM, TN) is the default wave split for that macro-tile.

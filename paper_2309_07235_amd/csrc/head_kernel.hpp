@@ -52,6 +52,7 @@ struct HeadArgs {
   int wait_target;
   int* done_counter;
   int* broken;      // set by a wait that gave up (see chain_wait)
+  long long wait_ticks;  // how long the wait may last, in ticks of the constant-rate wall clock
 };
 
 template <typename T, int KIND>
@@ -172,7 +173,7 @@ __global__ void __launch_bounds__(kHeadThreads) head_kernel(const HeadArgs<T> g)
 
   // The panel heads and the tile (requested above) do not depend on the diagonal block of this step,
   // the factors below do: the kernel is launched while that block is still being factored.
-  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, tid);
+  if (g.wait_counter) chain_wait(g.wait_counter, g.wait_target, g.broken, g.wait_ticks, tid);
 
   // ---- stage the factors: one element per thread and sub-block, all loads before the first LDS store
   {

@@ -17,13 +17,8 @@ namespace dla {
 template <typename T, int MODE>
 static int launch_prepare(const TriPrepareArgs<T>& a, hipStream_t st) {
   auto kern = tri_prepare_kernel<T, MODE>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            trisolve_lds_bytes<T>()) != hipSuccess)
-      return DLA_ERR_HIP;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;
+  if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), trisolve_lds_bytes<T>())) return DLA_ERR_HIP;
   const int grid = (int)((a.n + kNbMax - 1) / kNbMax);
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kTriThreads), trisolve_lds_bytes<T>(), st, a);

@@ -37,11 +37,6 @@
 #include <type_traits>
 #include "dla_common.hpp"
 
-// Optional phase tracing for development harnesses; expands to nothing in the library build.
-#ifndef DLA_TRACE
-#define DLA_TRACE(i)
-#endif
-
 namespace dla {
 
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
@@ -99,7 +94,6 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   const int64_t ld = g.ld;
   const int row0 = panel * kUpdRows;
 
-  DLA_TRACE(0);
   // ---- left panel -> registers (through LDS for coalesced global reads) -----------------------
   T afrag[KSTEPS];
   const int wrow0 = row0 + wave * 16;  // first row of this wave
@@ -195,10 +189,6 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // ---- C block of this wave: 16 rows x cols columns = NCB MFMA blocks ------------------------------
   T* const Cw = g.C + (int64_t)wrow0 * ld;
   auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
-#ifdef DLA_UPD_NO_CLOAD  // development switch: measure the kernel without its C reads
-    for (int q = 0; q < NCB; ++q) c[q] = acc_t{0, 0, 0, 0};
-    return;
-#endif
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
     if (full) {
 #pragma unroll
@@ -218,9 +208,6 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     }
   };
   auto store_c = [&](const acc_t (&c)[NCB], int j0) {
-#ifdef DLA_UPD_NO_STORE  // development switch: keep one store per wave so the work is not optimised away
-    if (j0 != col_begin) return;
-#endif
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
 #pragma unroll
     for (int q = 0; q < NCB; ++q) {
@@ -265,7 +252,6 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     if (have_done) store_c(done, jdone);
     if (jnn < col_end) fetch_c(tgt, jnn);
   };
-  DLA_TRACE(1);
   acc_t c0[NCB], c1[NCB], c2[NCB];
   fetch_b(col_begin);
   fetch_c(c0, col_begin);
@@ -275,22 +261,16 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     fetch_c(c1, col_begin + col_step);
   }
   lds_barrier();
-  DLA_TRACE(2);
   int buf = 0;
   // One block step.  cur holds this block's C; tgt is the set that becomes free in this step and
   // receives the C block two steps ahead.  Group 0 frees cur's predecessor itself (it stores right
   // after multiplying); for group 1 the previous block's result still sits in tgt when the step begins.
   auto block_step = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp, int jc, bool first, int b_) {
     if (grp == 0) {
-      DLA_TRACE(8);
       multiply(cur, b_);
-      DLA_TRACE(9);
       lds_barrier();  // Y
-      DLA_TRACE(10);
       side_work(cur, jc, true, tgt, jc, b_);
-      DLA_TRACE(11);
       lds_barrier();  // X
-      DLA_TRACE(12);
     } else {
       side_work(tgt, jp, !first, tgt, jc, b_);
       lds_barrier();  // Y

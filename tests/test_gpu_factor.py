@@ -276,10 +276,36 @@ def test_indefinite_matrix_index_matches_oracle(B, oracle):
 
 
 def test_info_pointer_is_optional(B, oracle):
+    """Without an info pointer a wait that gives up could not be reported, so the pipeline (n above two
+    blocks) is then ordered by stream events even when in-kernel hand-over is asked for."""
     announce("info=NULL")
     A = inputs.general_dominant_matrix(90, 42)
     got, _ = _gpu_lu(B, A, want_info=False)
     _check_lu(oracle, got, A, 90)
+    A = inputs.general_dominant_matrix(700, 42)
+    got, _ = _gpu_lu(B, A, _fparams(B, 0, 1), want_info=False)
+    _check_lu(oracle, got, A, 700)
+    S = inputs.spd_matrix(700, 42)
+    got, _ = _gpu_chol(B, S, _fparams(B, 0, 1), want_info=False)
+    _check_chol(oracle, got, S, 700)
+
+
+def test_a_partly_named_update_schedule_runs_as_tiled_gemms(B, oracle):
+    """Any non-zero field of the update schedule selects the tiled GEMM (fields left 0 take the menu's defaults):
+    a search that varies tile_k or unroll_k alone must not time the default kernel at every point."""
+    announce("update schedule with tile_k only")
+    n = 900
+    A = inputs.general_dominant_matrix(n, 47)
+    for tile in ((0, 0, 32), (0, 0, 0, 2)):
+        for la in (0, 1):
+            B.profile_enable(True)
+            got, info = _gpu_lu(B, A, _fparams(B, 128, la, tile))
+            B.profile_enable(False)
+            _, bulk_launches, _ = B.profile_read(B.PHASE_UPDATE)
+            _, gemm_launches, _ = B.profile_read(B.PHASE_GEMM)
+            B.profile_read(B.PHASE_DIAG), B.profile_read(B.PHASE_TRSM)
+            assert info == 0 and bulk_launches == 0 and gemm_launches > 0
+            _check_lu(oracle, got, A, n)
 
 
 # ------------------------------------------------------------------ layout, streams, determinism
