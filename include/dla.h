@@ -173,6 +173,26 @@ int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* 
 size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt);
 
 /*
+ * mm3 for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as mm3 without
+ * the workspace: E and F live in a fixed scratch array that is part of the library's device image
+ * (DLA_MM3_NOALLOC_MAX_BYTES per GPU, held until the process ends).  The call allocates and frees nothing
+ * and enqueues the same two launches as mm3 on hip_stream.  The first call on a device looks the array's
+ * device address up once (hipGetSymbolAddress).
+ *   - Sizes whose E and F need more than DLA_MM3_NOALLOC_MAX_BYTES (mm3_workspace_bytes(ni, nj, nl, dt)
+ *     exceeds it) are refused with DLA_ERR_TOO_LARGE before any work is enqueued; the paper's extralarge
+ *     3mm (E 1600 x 1800, F 1800 x 2200 in fp64) fits.
+ *   - All calls on one GPU share the one array, which keeps the previous call's E and F (nothing in it
+ *     has to start at zero: every element a call reads it has written first).  Calls that overlap in
+ *     time on one GPU (different streams, or several host threads) race on it: serialise them, or use
+ *     mm3 with a workspace per call.
+ */
+#define DLA_MM3_NOALLOC_MAX_BYTES (64u << 20)
+int mm3_noalloc(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc,
+                const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj,
+                int64_t nm, int64_t nl, dla_dtype dt, const dla_mm3_params* p, void* hip_stream);
+
+/*
  * The GEMM building block of all three kernels, exported so that a search can
  * time one schedule in isolation.
  *   op 0:  C  = A*B            A m x k, B k x n

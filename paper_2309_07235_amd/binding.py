@@ -69,6 +69,9 @@ def _load() -> ctypes.CDLL:
     lib.mm3.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i64, i64, i64, ci,
                         ctypes.POINTER(Mm3Params), vp, sz, vp]
     lib.mm3.restype = ci
+    lib.mm3_noalloc.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i64, i64, i64, ci,
+                                ctypes.POINTER(Mm3Params), vp]
+    lib.mm3_noalloc.restype = ci
     lib.mm3_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.mm3_workspace_bytes.restype = sz
     lib.dla_gemm.argtypes = [ci, vp, i64, vp, i64, vp, i64, i64, i64, i64, ci, ctypes.POINTER(GemmParams), vp]
@@ -252,6 +255,24 @@ def mm3(a, b, c, d, g, p: Mm3Params | None = None, workspace=None, stream=None):
     _check(lib.mm3(ap, lda, bp, ldb, cp, ldc, dp, ldd, gp, ldg, ni, nk, nj, nm, nl, dt, _ref(p), wsp, wsb,
                    ctypes.c_void_p(_stream_ptr(stream))), "mm3")
     return ws
+
+
+MM3_NOALLOC_MAX_BYTES = 64 << 20
+
+
+def mm3_noalloc(a, b, c, d, g, p: Mm3Params | None = None, stream=None):
+    """mm3 with E and F in the library's fixed device scratch: no workspace, no allocation (see dla.h: mm3_noalloc)."""
+    ni, nk = a.shape
+    nk2, nj = b.shape
+    nj2, nm = c.shape
+    nm2, nl = d.shape
+    if nk != nk2 or nj != nj2 or nm != nm2 or tuple(g.shape) != (ni, nl):
+        raise ValueError("3mm shapes do not chain")
+    dt = _dtype_code(a)
+    (ap, lda), (bp, ldb), (cp, ldc), (dp, ldd), (gp, ldg) = (_matrix(x, n) for x, n in
+                                                             ((a, "a"), (b, "b"), (c, "c"), (d, "d"), (g, "g")))
+    _check(lib.mm3_noalloc(ap, lda, bp, ldb, cp, ldc, dp, ldd, gp, ldg, ni, nk, nj, nm, nl, dt, _ref(p),
+                           ctypes.c_void_p(_stream_ptr(stream))), "mm3_noalloc")
 
 
 def dla_gemm(op: int, a, b, c, p: GemmParams | None = None, stream=None):

@@ -216,6 +216,30 @@ static int mm3_impl(const T* A, int64_t lda, const T* B, int64_t ldb, const T* C
 
 static const int64_t kMaxDim = (int64_t)1 << 30;
 
+// ------------------------------------------------------------------ scratch of mm3_noalloc
+// E and F of a 3mm for callers that may not allocate: a fixed array in the device image, one copy per
+// GPU, held from the moment the library's code is loaded on that GPU until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device address it returns (one
+// per GPU) is what is passed to kernels.
+static __device__ __align__(256) unsigned char scratch[DLA_MM3_NOALLOC_MAX_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device), or null on failure.
+static void* scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 // Register-resident MFMA loop: what the matrix pipes sustain when nothing else limits them.
 template <typename T>
 __global__ void __launch_bounds__(256) mfma_peak_kernel(T* out, int iters) {
@@ -407,9 +431,11 @@ size_t mm3_workspace_bytes(int64_t ni, int64_t nj, int64_t nl, dla_dtype dt) {
   return L.e_bytes + L.f_bytes + 256;
 }
 
-int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc, const void* d_d,
-        int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm, int64_t nl,
-        dla_dtype dt, const dla_mm3_params* p, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+// Argument checks shared by mm3 and mm3_noalloc (everything but the workspace); resolves the three schedules.
+static int mm3_check_args(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc,
+                          const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj,
+                          int64_t nm, int64_t nl, dla_dtype dt, const dla_mm3_params* p, GemmSchedule* se,
+                          GemmSchedule* sf, GemmSchedule* sg) {
   if (ni < 0) return -11;
   if (nk < 0) return -12;
   if (nj < 0) return -13;
@@ -428,21 +454,51 @@ int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* 
   if (ldd < (nl > 0 ? nl : 1)) return -8;
   if (ni > 0 && nl > 0 && (!d_g || (uintptr_t)d_g % es)) return -9;
   if (ldg < (nl > 0 ? nl : 1)) return -10;
-  GemmSchedule se, sf, sg;
   int rc;
-  if ((rc = resolve_schedule(dt, p ? &p->e : nullptr, OP_ASSIGN, &se, ni, nj)) != DLA_SUCCESS) return rc;
-  if ((rc = resolve_schedule(dt, p ? &p->f : nullptr, OP_ASSIGN, &sf, nj, nl)) != DLA_SUCCESS) return rc;
-  if ((rc = resolve_schedule(dt, p ? &p->g : nullptr, OP_ASSIGN, &sg, ni, nl)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->e : nullptr, OP_ASSIGN, se, ni, nj)) != DLA_SUCCESS) return rc;
+  if ((rc = resolve_schedule(dt, p ? &p->f : nullptr, OP_ASSIGN, sf, nj, nl)) != DLA_SUCCESS) return rc;
+  return resolve_schedule(dt, p ? &p->g : nullptr, OP_ASSIGN, sg, ni, nl);
+}
+
+static int mm3_run(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc,
+                   const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm,
+                   int64_t nl, dla_dtype dt, const GemmSchedule& se, const GemmSchedule& sf, const GemmSchedule& sg,
+                   void* ws, hipStream_t st) {
+  if (dt == DLA_F64)
+    return mm3_impl<double>((const double*)d_a, lda, (const double*)d_b, ldb, (const double*)d_c, ldc,
+                            (const double*)d_d, ldd, (double*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, ws, st);
+  return mm3_impl<float>((const float*)d_a, lda, (const float*)d_b, ldb, (const float*)d_c, ldc, (const float*)d_d,
+                         ldd, (float*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, ws, st);
+}
+
+int mm3(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc, const void* d_d,
+        int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm, int64_t nl,
+        dla_dtype dt, const dla_mm3_params* p, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  GemmSchedule se, sf, sg;
+  const int rc = mm3_check_args(d_a, lda, d_b, ldb, d_c, ldc, d_d, ldd, d_g, ldg, ni, nk, nj, nm, nl, dt, p, &se, &sf, &sg);
+  if (rc != DLA_SUCCESS) return rc;
   const size_t need = mm3_workspace_bytes(ni, nj, nl, dt);
   const bool uses_ws = (ni > 0 && nl > 0 && nj > 0);
   if (uses_ws && (!d_workspace || workspace_bytes < need || (uintptr_t)d_workspace % 256)) return DLA_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (dt == DLA_F64)
-    return mm3_impl<double>((const double*)d_a, lda, (const double*)d_b, ldb, (const double*)d_c, ldc,
-                            (const double*)d_d, ldd, (double*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, d_workspace,
-                            st);
-  return mm3_impl<float>((const float*)d_a, lda, (const float*)d_b, ldb, (const float*)d_c, ldc, (const float*)d_d,
-                         ldd, (float*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, d_workspace, st);
+  return mm3_run(d_a, lda, d_b, ldb, d_c, ldc, d_d, ldd, d_g, ldg, ni, nk, nj, nm, nl, dt, se, sf, sg, d_workspace,
+                 static_cast<hipStream_t>(hip_stream));
+}
+
+int mm3_noalloc(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, const void* d_c, int64_t ldc,
+                const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm,
+                int64_t nl, dla_dtype dt, const dla_mm3_params* p, void* hip_stream) {
+  GemmSchedule se, sf, sg;
+  const int rc = mm3_check_args(d_a, lda, d_b, ldb, d_c, ldc, d_d, ldd, d_g, ldg, ni, nk, nj, nm, nl, dt, p, &se, &sf, &sg);
+  if (rc != DLA_SUCCESS) return rc;
+  // E and F must fit the fixed scratch
+  if (mm3_workspace_bytes(ni, nj, nl, dt) > (size_t)DLA_MM3_NOALLOC_MAX_BYTES) return DLA_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  if (ni > 0 && nl > 0 && nj > 0) {
+    ws = scratch_of_current_device();
+    if (!ws) return DLA_ERR_HIP;
+  }
+  return mm3_run(d_a, lda, d_b, ldb, d_c, ldc, d_d, ldd, d_g, ldg, ni, nk, nj, nm, nl, dt, se, sf, sg, ws,
+                 static_cast<hipStream_t>(hip_stream));
 }
 
 static int factor_common_checks(void* d_a, int64_t n, int64_t lda, dla_dtype dt) {

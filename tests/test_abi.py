@@ -134,6 +134,22 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert mm3(p=ctypes.byref(badp)) == B.DLA_ERR_UNSUPPORTED_PARAMS
     assert mm3(dims=(0, 8, 8, 8, 8), a=None, g=None, ws=None, wsb=0) == 0  # empty G: nothing to do
 
+    def mm3n(a=fake, lda=8, g=fake, ldg=8, dims=(8, 8, 8, 8, 8), dt=B.DLA_F64, p=None):
+        return L.mm3_noalloc(a, lda, fake, 8, fake, 8, fake, 8, g, ldg, *dims, dt, p, None)
+
+    # the entry point that allocates nothing: same argument checks, and sizes beyond its fixed scratch are refused
+    assert mm3n(a=None) == -1
+    assert mm3n(lda=7) == -2
+    assert mm3n(g=None) == -9
+    assert mm3n(dims=(8, 8, -1, 8, 8)) == -13
+    assert mm3n(dt=9) == -16
+    assert mm3n(p=ctypes.byref(badp)) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    big = (3000, 8, 3000, 8, 3000)  # E and F: 2 * 3000 * 3008 * 8 bytes > 64 MiB
+    assert B.mm3_workspace_bytes(3000, 3000, 3000, B.DLA_F64) > B.MM3_NOALLOC_MAX_BYTES
+    assert L.mm3_noalloc(fake, 8, fake, 3000, fake, 8, fake, 3000, fake, 3000, *big, B.DLA_F64, None, None) == B.DLA_ERR_TOO_LARGE
+    assert B.mm3_workspace_bytes(1600, 1800, 2200, B.DLA_F64) <= B.MM3_NOALLOC_MAX_BYTES  # the extralarge 3mm fits
+    assert mm3n(dims=(0, 8, 8, 8, 8), a=None, g=None) == 0  # empty G: nothing to do, the scratch is not looked up
+
     for solve in (L.lu_solve, L.cholesky_solve):
         assert solve(None, 8, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -1
         assert solve(vp(0x1004), 8, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 20, None) == -1  # misaligned
