@@ -170,8 +170,8 @@ def main(argv=None) -> int:
     kernels = {}
     upd_ms = upd_fl = 0.0
     upd_launches = 0
-    runs = (("lu", lambda r: B.lu_factor(lu_bufs[r], p_lu, workspace=ws_f), lu_flops(n), lu_bufs, d_lu0),
-            ("cholesky", lambda r: B.cholesky_factor(ch_bufs[r], p_ch, workspace=ws_f), chol_flops(n), ch_bufs, d_ch0),
+    runs = (("lu", lambda r: B.lu_factor(lu_bufs[r], p_lu, workspace=ws_f, info=info[0:1]), lu_flops(n), lu_bufs, d_lu0),
+            ("cholesky", lambda r: B.cholesky_factor(ch_bufs[r], p_ch, workspace=ws_f, info=info[1:2]), chol_flops(n), ch_bufs, d_ch0),
             ("mm3", lambda r: B.mm3(*d_ops, d_g, p_mm, workspace=ws_m), mm3_flops(dims), None, None))
 
     def phase(ph, reps):

@@ -228,13 +228,14 @@ def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str =
     space = SearchSpace(["nb", "lookahead", "update"], [list(range(16, 129, 16)), [0, 1], updates],
                         legal=lambda c: kind == "lu" or c["update"][0] == c["update"][1])  # Cholesky: square tiles
     ws = torch.empty(B.factor_workspace_bytes(n, dt, None), dtype=torch.uint8, device="cuda")
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")  # look-ahead 1 hands over inside kernels only with an info pointer
 
     def objective(cfg):
         p = B.FactorParams(cfg["nb"], cfg["lookahead"], B.GemmParams(*cfg["update"]))
 
         def call():
             work.copy_(src)  # in place: restore the input (a device copy, part of every evaluation alike)
-            fn(work, p, workspace=ws)
+            fn(work, p, workspace=ws, info=info)
 
         return _time_ms(call, reps)
 
