@@ -30,12 +30,19 @@ METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
 UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 67239 * 1024
 
 
-def update_algorithmic_bytes(n, nb=128, lower=False):
+def update_algorithmic_bytes(n, nb=128, lower=False, defer_min_rows=0):
     """(launches, bytes) the bulk updates of one factorisation must move: every element of the region
     read and written once, the panels read once (blocks of 128 rows for the lower-triangular case).
-    Mirrors the library's schedule: while the trailing matrix is large (3072 rows for LU, 4096 for
-    Cholesky, block size 128) every other step puts its bulk update off and the next one applies both
-    panels at once, to the region behind block N3."""
+    Mirrors the library's schedule (dla.h, dla_factor_params): sub-panels of nb (nb / 2 for block sizes
+    above 128); while the trailing matrix has at least the deferral threshold of rows every other step
+    puts its bulk update off and the next one applies both sub-panels at once, to the region behind
+    block N3."""
+    two_level = nb > 128 or (nb == 128 and defer_min_rows != -1)
+    if nb > 128:
+        nb, min_rows = nb // 2, 0
+    else:
+        min_rows = defer_min_rows if defer_min_rows > 0 else (4096 if lower else 3072)
+
     def region(rows, lead):
         if lower:
             elems = sum(min(128, rows - r0) * min(r0 + 128, rows) for r0 in range(0, rows, 128))
@@ -54,7 +61,7 @@ def update_algorithmic_bytes(n, nb=128, lower=False):
         bn2 = min(nb, mr)
         if mr > bn2:
             rest = mr - bn2
-            if not owed and nb == 128 and mr >= (4096 if lower else 3072) and rest >= 4 * nb:
+            if not owed and two_level and mr >= min_rows and rest >= 4 * nb:
                 owed = True
             else:
                 rows, depth, lead = (rest, 2 * nb, min(nb, rest)) if owed else (mr, nb, bn2)
@@ -204,8 +211,8 @@ def main(argv=None) -> int:
         upd_launches += ucnt
     achieved = upd_fl / upd_ms * 1e-9 if upd_ms > 0 else 0.0  # TFLOP/s
     measured_peak = B.mfma_peak(B.DLA_F64)  # register-resident MFMA loop, the achievable counterpart of the published peak
-    la, ba = update_algorithmic_bytes(n, p_lu.nb or 128, False)
-    lc, bc = update_algorithmic_bytes(n, p_ch.nb or 128, True)
+    la, ba = update_algorithmic_bytes(n, p_lu.nb or 128, False, p_lu.defer_min_rows)
+    lc, bc = update_algorithmic_bytes(n, p_ch.nb or 128, True, p_ch.defer_min_rows)
     alg_launches, alg_bytes = la + lc, ba + bc
 
     # ---- CPU oracle on the host cores: one pass of the same workload ----------------------------
@@ -225,8 +232,10 @@ def main(argv=None) -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"lu_factor N={n} + cholesky_factor N={n} + mm3 1600x2000x1800x2400x2200 per step",
-                   "lu": {"nb": p_lu.nb, "lookahead": p_lu.lookahead, "update": p_lu.update.as_tuple()},
-                   "cholesky": {"nb": p_ch.nb, "lookahead": p_ch.lookahead, "update": p_ch.update.as_tuple()},
+                   "lu": {"nb": p_lu.nb, "lookahead": p_lu.lookahead, "update": p_lu.update.as_tuple(),
+                          "defer_min_rows": p_lu.defer_min_rows},
+                   "cholesky": {"nb": p_ch.nb, "lookahead": p_ch.lookahead, "update": p_ch.update.as_tuple(),
+                                "defer_min_rows": p_ch.defer_min_rows},
                    "mm3": {"e": p_mm.e.as_tuple(), "f": p_mm.f.as_tuple(), "g": p_mm.g.as_tuple()}},
         "pct_of_fp64_mfma_peak": round(gflops * 1e-3 / PEAK_F64_MFMA_TFLOPS * 100, 2),
         "measured_fp64_mfma_peak_tflops": round(measured_peak, 2),

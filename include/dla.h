@@ -76,12 +76,25 @@ typedef struct {
 /*
  * Schedule of a blocked right-looking factorisation.  nb is the panel width
  * (block size), update the schedule of the trailing-matrix update
- * A22 -= L21 * U12 (lower(A22) -= L21 * L21^T for Cholesky) that dominates the run time: all fields 0 (the default) selects the
- * library's panel-stationary rank-nb update kernel, anything else runs the
- * update as tiled GEMMs with that schedule, so that a search can drive it.
+ * A22 -= L21 * U12 (lower(A22) -= L21 * L21^T for Cholesky) that dominates the run time:
+ * all six fields 0 (the default) selects the
+ * library's panel-stationary rank-nb update kernel; if any field is set the
+ * update runs as tiled GEMMs with that schedule (fields left 0 take the menu's
+ * defaults), so that a search can drive each of them.
+ *
+ * Block sizes.  16 .. 128 in steps of 16: one level of blocking, the diagonal block is factored by one
+ * workgroup out of LDS (128 x 128 fp64 is what fits).  160, 192, 224, 256: two levels.  The panel of nb
+ * columns is factored as two sub-panels of nb / 2, and the bulk of the trailing matrix receives both
+ * at once in one update of depth nb (twice the flops per byte of the trailing matrix); these need the
+ * look-ahead pipeline and the default update kernel, otherwise DLA_ERR_UNSUPPORTED_PARAMS.  With
+ * nb = 128 the same two-level form (depth 256, sub-panels of 128) is used on its own accord while the
+ * trailing matrix is large; defer_min_rows moves that threshold.
+ *
+ * There is no separate inner block size of the diagonal-block kernel: it works in stages of 16 columns,
+ * the edge of the MFMA block, and nothing else is instantiated.
  */
 typedef struct {
-  int nb;        /* block size, multiple of 16, 16..128 (0 = default)                          */
+  int nb;        /* block size (0 = default 128); see above                                     */
   int lookahead; /* 0: one stream, strictly sequential steps; 1: the next diagonal block is factored
                     while panel solves and trailing update of this step run on helper streams, and
                     the kernels of that chain wait for each other inside the kernels (needs kernels
@@ -89,6 +102,9 @@ typedef struct {
                     events only, for tools that serialise kernels (hardware-counter profiling,
                     debuggers); -1 = default (1)                                                */
   dla_gemm_params update;
+  int defer_min_rows; /* nb = 128 only: bulk updates run two panels deep while the trailing matrix has
+                         at least this many rows.  0 = library default (3072 for LU, 4096 for Cholesky),
+                         -1 = never, 1 = whenever possible.  Ignored for other block sizes.      */
 } dla_factor_params;
 
 /* The six tile parameters of the 3mm code mold: (P0,P1) -> e, (P2,P3) -> f, (P4,P5) -> g. */
@@ -235,7 +251,7 @@ int dla_gemm_params_supported(dla_dtype dt, const dla_gemm_params* p);
  */
 int dla_enumerate_tiles(dla_dtype dt, dla_gemm_params* out, int cap);
 
-/* 1 if nb is a legal block size for the factorisations, else 0. */
+/* 1 if nb is a legal block size for the factorisations (16 .. 128 step 16; 160, 192, 224, 256), else 0. */
 int dla_block_size_supported(dla_dtype dt, int nb);
 
 /*

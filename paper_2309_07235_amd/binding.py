@@ -34,7 +34,8 @@ class GemmParams(ctypes.Structure):
 
 
 class FactorParams(ctypes.Structure):
-    _fields_ = [("nb", ctypes.c_int), ("lookahead", ctypes.c_int), ("update", GemmParams)]
+    _fields_ = [("nb", ctypes.c_int), ("lookahead", ctypes.c_int), ("update", GemmParams),
+                ("defer_min_rows", ctypes.c_int)]
 
 
 class Mm3Params(ctypes.Structure):

@@ -327,7 +327,7 @@ int dla_enumerate_tiles(dla_dtype dt, dla_gemm_params* out, int cap) {
 
 int dla_block_size_supported(dla_dtype dt, int nb) {
   if (dt != DLA_F64 && dt != DLA_F32) return 0;
-  return (nb >= 16 && nb <= 128 && nb % 16 == 0) ? 1 : 0;
+  return ((nb >= 16 && nb <= 128 && nb % 16 == 0) || (nb > 128 && nb <= 256 && nb % 32 == 0)) ? 1 : 0;
 }
 
 int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
@@ -344,15 +344,16 @@ int dla_default_params(int kernel, int64_t n, dla_dtype dt, void* out) {
     return DLA_SUCCESS;
   }
   dla_factor_params* p = static_cast<dla_factor_params*>(out);
-  int nb, la;
+  FactorPlan plan;
   GemmSchedule s;
   const int op = kernel == DLA_KERNEL_LU ? OP_SUB : OP_SUB_NT_LOWER;
-  int rc = resolve_factor_params(dt, n, nullptr, op, &nb, &la, &s);
+  int rc = resolve_factor_params(dt, n, nullptr, op, &plan, &s);
   if (rc != DLA_SUCCESS) return rc;
-  p->nb = nb;
-  p->lookahead = la;
+  p->nb = plan.nb_outer;
+  p->lookahead = plan.lookahead;
   (void)s;
   p->update = dla_gemm_params{0, 0, 0, 0, 0, 0};  // the panel-stationary update kernel
+  p->defer_min_rows = 0;
   return DLA_SUCCESS;
 }
 

@@ -34,17 +34,28 @@ size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_par
   return 4 * inv_set_bytes(dt) + 4 * head_copy_bytes(dt) + 256;  // + the hand-over counters of the latency chain
 }
 
-int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
+int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, FactorPlan* plan,
                           GemmSchedule* upd) {
   (void)n;
   int b = in ? in->nb : 0;
   if (b == 0) b = 128;
-  if (b < 16 || b > kNbMax || b % 16 != 0) return DLA_ERR_UNSUPPORTED_PARAMS;
+  const bool one_level = b >= 16 && b <= kNbMax && b % 16 == 0;
+  const bool two_level = b > kNbMax && b <= 2 * kNbMax && b % 32 == 0;
+  if (!one_level && !two_level) return DLA_ERR_UNSUPPORTED_PARAMS;
   int la = in ? in->lookahead : -1;
   if (la < -1 || la > 2) return DLA_ERR_UNSUPPORTED_PARAMS;
   if (la == -1) la = 1;
-  *nb = b;
-  *lookahead = la;
+  const int defer = in ? in->defer_min_rows : 0;
+  if (defer < -1) return DLA_ERR_UNSUPPORTED_PARAMS;
+  const bool tiled = in && (in->update.tile_m != 0 || in->update.tile_n != 0 || in->update.tile_k != 0 ||
+                            in->update.unroll_k != 0 || in->update.wave_m != 0 || in->update.wave_n != 0);
+  // two sub-panels per panel need the pipeline's deferred bulk update and the kernel that takes depth 256
+  if (two_level && (la == 0 || tiled)) return DLA_ERR_UNSUPPORTED_PARAMS;
+  plan->nb_outer = b;
+  plan->nb = two_level ? b / 2 : b;
+  plan->lookahead = la;
+  plan->two_level = two_level || (b == kNbMax && defer != -1 && !tiled);
+  plan->defer_min_rows = two_level ? 0 : (defer > 0 ? defer : (op == OP_SUB ? kDeferMinRowsLu : kDeferMinRowsChol));
   return resolve_schedule(dt, in ? &in->update : nullptr, op, upd);
 }
 
@@ -259,11 +270,12 @@ template <typename T, int KIND>
 static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p, void* ws, size_t ws_bytes,
                        hipStream_t st, int* d_info) {
   const dla_dtype dt = sizeof(T) == 8 ? DLA_F64 : DLA_F32;
-  int nb, lookahead;
+  FactorPlan plan;
   GemmSchedule upd;
   const int op = (KIND == KIND_LU) ? OP_SUB : OP_SUB_NT_LOWER;
-  int rc = resolve_factor_params(dt, n, p, op, &nb, &lookahead, &upd);
+  int rc = resolve_factor_params(dt, n, p, op, &plan, &upd);
   if (rc != DLA_SUCCESS) return rc;
+  const int nb = plan.nb, lookahead = plan.lookahead;  // nb: the sub-panel one diagonal-block kernel factors
   if (n == 0) return DLA_SUCCESS;
   if (!ws || ws_bytes < factor_workspace_bytes_impl(n, dt, p) || ((uintptr_t)ws % 256)) return DLA_ERR_WORKSPACE;
   // the panel-stationary update kernel unless the caller names any field of a tiled schedule
@@ -509,7 +521,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
         const int64_t rest = mr - bn2;
         // put the bulk update off when the step after this one can carry it: full blocks N2, N3 and
         // two more behind them, and a trailing matrix large enough for the bulk stream to be the longest
-        if (!owed && auto_tile && nb == kNbMax && mr >= (KIND == KIND_LU ? kDeferMinRowsLu : kDeferMinRowsChol) && rest >= 4 * (int64_t)nb) {
+        if (!owed && auto_tile && plan.two_level && mr >= plan.defer_min_rows && rest >= 4 * (int64_t)nb) {
           owed = true;
           after_wide = false;
           return DLA_SUCCESS;

@@ -82,7 +82,15 @@ size_t solve_workspace_bytes_impl(int64_t n, int64_t nrhs, dla_dtype dt);
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p);
 constexpr size_t kHandoverSelftestBytes = 8192;
 int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info);
-int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, int* nb, int* lookahead,
+// What a dla_factor_params resolves to.  nb: the width of the sub-panel one diagonal-block kernel factors
+// (= nb_outer up to 128, else half of it); two_level: bulk updates may run two sub-panels deep, while the
+// trailing matrix has at least defer_min_rows rows.
+struct FactorPlan {
+  int nb_outer, nb, lookahead;
+  bool two_level;
+  int64_t defer_min_rows;
+};
+int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, int op, FactorPlan* plan,
                           GemmSchedule* upd);
 
 }  // namespace dla

@@ -212,8 +212,9 @@ def mm3_problem(dims: Dict[str, int], seed: int = 4, reps: int = 5, dtype: str =
 
 
 def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str = "f64"):
-    """Search space and objective of lu_factor / cholesky_factor: block size, look-ahead, and the trailing-update
-    schedule (entry 0 = the library's own update kernel, the others = tiled GEMM schedules of the menu)."""
+    """Search space and objective of lu_factor / cholesky_factor: block size (one level up to 128, two sub-panels
+    above), look-ahead, the trailing-update schedule (entry 0 = the library's own update kernel, the others = tiled
+    GEMM schedules of the menu), and the size from which bulk updates run two panels deep."""
     import torch
     from . import binding as B
     from . import inputs
@@ -225,13 +226,21 @@ def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str =
     work = torch.empty_like(src)
     fn = B.lu_factor if kind == "lu" else B.cholesky_factor
     updates = [(0, 0, 0, 0, 0, 0)] + [t.as_tuple() for t in B.enumerate_tiles(dt)]
-    space = SearchSpace(["nb", "lookahead", "update"], [list(range(16, 129, 16)), [0, 1], updates],
-                        legal=lambda c: kind == "lu" or c["update"][0] == c["update"][1])  # Cholesky: square tiles
+    def legal(c):
+        if c["nb"] > 128 and (c["lookahead"] == 0 or any(c["update"])):
+            return False  # two sub-panels per panel need the pipeline and the library's own update kernel
+        if c["defer_min_rows"] != 0 and (c["nb"] != 128 or any(c["update"])):
+            return False  # the threshold only exists for block size 128 (keeps the space free of duplicates)
+        return kind == "lu" or c["update"][0] == c["update"][1]  # Cholesky: square tiles
+
+    space = SearchSpace(["nb", "lookahead", "update", "defer_min_rows"],
+                        [list(range(16, 129, 16)) + [160, 192, 224, 256], [0, 1], updates, [0, -1, 1, 1024, 2048]],
+                        legal=legal)
     ws = torch.empty(B.factor_workspace_bytes(n, dt, None), dtype=torch.uint8, device="cuda")
     info = torch.zeros(1, dtype=torch.int32, device="cuda")  # look-ahead 1 hands over inside kernels only with an info pointer
 
     def objective(cfg):
-        p = B.FactorParams(cfg["nb"], cfg["lookahead"], B.GemmParams(*cfg["update"]))
+        p = B.FactorParams(cfg["nb"], cfg["lookahead"], B.GemmParams(*cfg["update"]), cfg["defer_min_rows"])
 
         def call():
             work.copy_(src)  # in place: restore the input (a device copy, part of every evaluation alike)
@@ -240,7 +249,8 @@ def factor_problem(kind: str, n: int, seed: int = 5, reps: int = 3, dtype: str =
         return _time_ms(call, reps)
 
     d = B.default_params(B.DLA_KERNEL_LU if kind == "lu" else B.DLA_KERNEL_CHOLESKY, n, dt)
-    return space, objective, {"nb": d.nb, "lookahead": d.lookahead, "update": d.update.as_tuple()}
+    return space, objective, {"nb": d.nb, "lookahead": d.lookahead, "update": d.update.as_tuple(),
+                              "defer_min_rows": d.defer_min_rows}
 
 
 def main(argv=None) -> int:

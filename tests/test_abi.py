@@ -66,7 +66,8 @@ def test_tile_menu_queries(B):
 
 def test_block_sizes(B):
     legal = [nb for nb in range(0, 300) if B.block_size_supported(B.DLA_F64, nb)]
-    assert legal == list(range(16, 129, 16))
+    assert legal == list(range(16, 129, 16)) + [160, 192, 224, 256]  # above 128: two sub-panels of nb / 2
+    assert legal == [nb for nb in range(0, 300) if B.block_size_supported(B.DLA_F32, nb)]
 
 
 def test_default_params(B):
@@ -100,6 +101,10 @@ def test_argument_errors_are_reported_without_gpu_work(B):
     assert L.lu_factor(vp(0x1004), 8, 8, B.DLA_F64, None, fake, 1 << 20, None, None) == -1  # misaligned
     bad = B.FactorParams(100, 0, B.GemmParams(0, 0, 0, 0, 0, 0))
     assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
+    for nb, la, tile, defer in ((144, 1, 0, 0), (272, 1, 0, 0), (256, 0, 0, 0), (192, 1, 64, 0), (128, 1, 0, -2)):
+        # not a two-level size; too wide; two levels need the pipeline, and the default update kernel; bad threshold
+        bad = B.FactorParams(nb, la, B.GemmParams(tile, tile, 0, 0, 0, 0), defer)
+        assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
     bad = B.FactorParams(64, 3, B.GemmParams(0, 0, 0, 0, 0, 0))  # look-ahead modes are 0, 1, 2
     assert L.lu_factor(fake, 8, 8, B.DLA_F64, ctypes.byref(bad), fake, 1 << 20, None, None) == B.DLA_ERR_UNSUPPORTED_PARAMS
     bad = B.FactorParams(64, 0, B.GemmParams(48, 48, 0, 0, 0, 0))

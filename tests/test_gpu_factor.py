@@ -26,9 +26,9 @@ def B():
     return binding
 
 
-def _fparams(B, nb=0, lookahead=-1, tile=None):
+def _fparams(B, nb=0, lookahead=-1, tile=None, defer_min_rows=0):
     t = B.GemmParams(*(tile or (0, 0)), *([0] * (6 - len(tile or (0, 0)))))
-    return B.FactorParams(nb, lookahead, t)
+    return B.FactorParams(nb, lookahead, t, defer_min_rows)
 
 
 def _gpu_lu(B, A, params=None, dtype=None, want_info=True):
@@ -220,6 +220,69 @@ def test_sizes_around_the_two_level_bulk_update(B, oracle, kind, n):
         got, info = _gpu_chol(B, A)
         assert info == 0
         _check_chol(oracle, got, A, n)
+
+
+@pytest.mark.parametrize("nb", [160, 192, 224, 256])
+@pytest.mark.parametrize("n", [700, 2100])
+def test_two_level_block_sizes(B, oracle, nb, n):
+    """Block sizes above 128: panels of two sub-panels, bulk updates of depth nb.  Element by element against the
+    oracle in fp64, and in fp32 against the fp64 oracle on the fp32-rounded input; sizes with a ragged last block,
+    both look-ahead modes of the pipeline."""
+    import torch
+    announce(f"two-level nb={nb} n={n}")
+    A = inputs.general_dominant_matrix(n, 90 + nb)
+    S = inputs.spd_matrix(n, 91 + nb)
+    for la in (1, 2):
+        got, info = _gpu_lu(B, A, _fparams(B, nb, la))
+        assert info == 0
+        _check_lu(oracle, got, A, n)
+        got, info = _gpu_chol(B, S, _fparams(B, nb, la))
+        assert info == 0
+        _check_chol(oracle, got, S, n)
+    A32, S32 = A.astype(np.float32), S.astype(np.float32)
+    got, info = _gpu_lu(B, A32, _fparams(B, nb), dtype=torch.float32)
+    assert info == 0 and got.dtype == np.float32
+    _check_lu(oracle, got.astype(np.float64), A32.astype(np.float64), n, TOL32, EPS32)
+    got, info = _gpu_chol(B, S32, _fparams(B, nb), dtype=torch.float32)
+    assert info == 0
+    _check_chol(oracle, got.astype(np.float64), S32.astype(np.float64), n, TOL32, EPS32)
+
+
+@pytest.mark.parametrize("defer", [-1, 1, 1024])
+def test_deferral_threshold_is_a_parameter(B, oracle, defer):
+    """nb = 128 with the two-level bulk update never, always, and from 1024 rows on: same factors to rounding;
+    the number of bulk launches shows which schedule ran."""
+    announce(f"defer_min_rows={defer}")
+    n = 2500
+    A = inputs.diag_dominant_matrix(n, 95)
+    S = inputs.spd_matrix(n, 96)
+    B.profile_enable(True)
+    got, info = _gpu_lu(B, A, _fparams(B, 128, 1, None, defer))
+    B.profile_enable(False)
+    _, launches, _ = B.profile_read(B.PHASE_UPDATE)
+    for ph in (B.PHASE_GEMM, B.PHASE_DIAG, B.PHASE_TRSM):
+        B.profile_read(ph)
+    assert info == 0
+    _check_lu(oracle, got, A, n)
+    steps = (n + 127) // 128 - 1
+    if defer == -1:
+        assert launches >= steps - 2
+    elif defer == 1:
+        assert launches <= steps // 2 + 3
+    got, info = _gpu_chol(B, S, _fparams(B, 128, 1, None, defer))
+    assert info == 0
+    _check_chol(oracle, got, S, n)
+
+
+def test_min_index_matrix_is_bit_exact_with_two_levels(B):
+    announce("min-index exact, nb=256 and nb=192, n=3000")
+    n = 3000
+    A = inputs.min_index_matrix(n)
+    for nb in (256, 192):
+        got, info = _gpu_lu(B, A, _fparams(B, nb))
+        assert info == 0 and np.array_equal(got, np.ones((n, n)))
+        got, info = _gpu_chol(B, A, _fparams(B, nb))
+        assert info == 0 and np.array_equal(got, np.tril(np.ones((n, n))))
 
 
 # ------------------------------------------------------------------ schedules
