@@ -294,6 +294,12 @@ size_t dla_mfma_peak_scratch_bytes(void);
 int dla_handover_selftest(void* d_scratch, size_t scratch_bytes, void* hip_stream, int* d_info);
 
 const char* dla_strerror(int code);
+/*
+ * After an entry point returned DLA_ERR_HIP on this host thread: which HIP error it was and in which of
+ * the library's launch functions ("hipErrorX (code) in function"); "" if there was none.  The string is
+ * owned by the library and overwritten by the next call on the same thread.
+ */
+const char* dla_last_error_detail(void);
 const char* dla_version(void);
 
 #ifdef __cplusplus

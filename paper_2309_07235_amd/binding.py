@@ -11,6 +11,11 @@ from __future__ import annotations
 import ctypes
 from pathlib import Path
 
+# torch first: its wheel carries a HIP runtime of its own, and the streams and device pointers handed to this
+# library belong to that runtime.  Loaded after it, the library's reference to the runtime resolves to the copy
+# already in the process; loaded before it, the process would hold two runtimes that do not know of each other.
+import torch  # noqa: F401
+
 _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "libdla_mi355x.so"
 
@@ -45,7 +50,8 @@ class Mm3Params(ctypes.Structure):
 class DlaError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: code {code}: {strerror(code)}")
+        detail = lib.dla_last_error_detail().decode() if code == DLA_ERR_HIP else ""
+        super().__init__(f"{where}: code {code}: {strerror(code)}" + (f" [{detail}]" if detail else ""))
 
 
 def _load() -> ctypes.CDLL:
@@ -100,6 +106,8 @@ def _load() -> ctypes.CDLL:
     lib.dla_profile_read.restype = ci
     lib.dla_strerror.argtypes = [ci]
     lib.dla_strerror.restype = ctypes.c_char_p
+    lib.dla_last_error_detail.argtypes = []
+    lib.dla_last_error_detail.restype = ctypes.c_char_p
     lib.dla_version.argtypes = []
     lib.dla_version.restype = ctypes.c_char_p
     return lib

@@ -1,6 +1,7 @@
 // C-ABI entry points (see include/dla.h): argument validation, schedule
 // resolution, 3mm driver, GEMM export, profiler.  Argument errors are reported
 // before any HIP call so they can be exercised on a machine without a GPU.
+#include <cstdio>
 #include <mutex>
 #include <vector>
 #include "host_common.hpp"
@@ -162,7 +163,7 @@ static int fill_zero(T* c, int64_t ld, int64_t rows, int64_t cols, hipStream_t s
   const int64_t total = rows * cols;
   hipLaunchKernelGGL(fill_zero_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, c, ld, (int)rows,
                      (int)cols);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -293,6 +294,14 @@ using namespace dla;
 
 extern "C" {
 
+const char* dla_last_error_detail(void) {
+  static thread_local char text[160];
+  if (tl_hip_error.code == hipSuccess) return "";
+  snprintf(text, sizeof(text), "%s (%d) in %s", hipGetErrorName(tl_hip_error.code), (int)tl_hip_error.code,
+           tl_hip_error.where);
+  return text;
+}
+
 const char* dla_version(void) { return "dla-mi355x 0.1 (gfx950, MFMA 16x16x4)"; }
 
 const char* dla_strerror(int code) {
@@ -379,6 +388,7 @@ int dla_gemm(int op, const void* d_a, int64_t lda, const void* d_b, int64_t ldb,
   GemmSchedule s;
   int rc = resolve_schedule(dt, p, op, &s, m, n);
   if (rc != DLA_SUCCESS) return rc;
+  hip_clear_stale_error();
   if (op == OP_SUB_TN) {  // instantiated for the 32x32 (16x16 waves) and 64x64 (32x32 waves) macro-tiles only
     if (!p || (p->tile_m == 0 && p->tile_n == 0)) s = GemmSchedule{64, 64, 16, 2, 32, 32};
     const bool ok = (s.tm == 32 && s.tn == 32 && s.wm == 16 && s.wn == 16) || (s.tm == 64 && s.tn == 64 && s.wm == 32 && s.wn == 32);
@@ -403,6 +413,7 @@ int dla_rank_update(int lower, const void* d_l, const void* d_r, void* d_c, int6
   if (dt != DLA_F64 && dt != DLA_F32) return -8;
   if (m > kMaxDim) return DLA_ERR_TOO_LARGE;
   if (m == 0 || k == 0) return DLA_SUCCESS;
+  hip_clear_stale_error();
   const size_t es = (size_t)esize(dt);
   if (!d_l || (uintptr_t)d_l % es) return -2;
   if (!lower && (!d_r || (uintptr_t)d_r % es)) return -3;
@@ -465,6 +476,7 @@ static int mm3_run(const void* d_a, int64_t lda, const void* d_b, int64_t ldb, c
                    const void* d_d, int64_t ldd, void* d_g, int64_t ldg, int64_t ni, int64_t nk, int64_t nj, int64_t nm,
                    int64_t nl, dla_dtype dt, const GemmSchedule& se, const GemmSchedule& sf, const GemmSchedule& sg,
                    void* ws, hipStream_t st) {
+  hip_clear_stale_error();
   if (dt == DLA_F64)
     return mm3_impl<double>((const double*)d_a, lda, (const double*)d_b, ldb, (const double*)d_c, ldc,
                             (const double*)d_d, ldd, (double*)d_g, ldg, ni, nk, nj, nm, nl, se, sf, sg, ws, st);
@@ -521,6 +533,7 @@ int lu_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_factor_
               size_t workspace_bytes, void* hip_stream, int* d_info) {
   int rc = factor_common_checks(d_a, n, lda, dt);
   if (rc != DLA_SUCCESS) return rc;
+  hip_clear_stale_error();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == DLA_F64) return lu_factor_impl<double>((double*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
   return lu_factor_impl<float>((float*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
@@ -530,6 +543,7 @@ int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_f
                     size_t workspace_bytes, void* hip_stream, int* d_info) {
   int rc = factor_common_checks(d_a, n, lda, dt);
   if (rc != DLA_SUCCESS) return rc;
+  hip_clear_stale_error();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == DLA_F64)
     return cholesky_factor_impl<double>((double*)d_a, n, lda, p, d_workspace, workspace_bytes, st, d_info);
@@ -558,6 +572,7 @@ int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, 
              void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = solve_common_checks(d_lu, n, lda, d_b, nrhs, ldb, dt);
   if (rc != DLA_SUCCESS) return rc;
+  hip_clear_stale_error();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == DLA_F64)
     return solve_impl<double, 0>((const double*)d_lu, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
@@ -568,6 +583,7 @@ int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t n
                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = solve_common_checks(d_l, n, lda, d_b, nrhs, ldb, dt);
   if (rc != DLA_SUCCESS) return rc;
+  hip_clear_stale_error();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == DLA_F64)
     return solve_impl<double, 1>((const double*)d_l, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
@@ -578,6 +594,7 @@ int dla_handover_selftest(void* d_scratch, size_t scratch_bytes, void* hip_strea
   if (!d_scratch || ((uintptr_t)d_scratch % 256)) return -1;
   if (scratch_bytes < kHandoverSelftestBytes) return -2;
   if (!d_info) return -4;
+  hip_clear_stale_error();
   return handover_selftest_impl(d_scratch, static_cast<hipStream_t>(hip_stream), d_info);
 }
 

@@ -74,7 +74,7 @@ static int launch_diag(const DiagArgs<T>& a, hipStream_t st, hipEvent_t done = n
   if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), diag_lds_bytes<T>())) return DLA_ERR_HIP;
   ProfileScope scope(PHASE_DIAG, 0.0, st);
   launch_ev(kern, dim3(1), dim3(kDiagThreads), diag_lds_bytes<T>(), st, done, a);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 // Rank-b trailing update with the panel-stationary kernel (see update_kernel.hpp): one launch over
@@ -113,13 +113,13 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
       hipEvent_t p0 = nullptr, p1 = nullptr;
       if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
         hipExtLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, p0, p1, 0, a, total_blocks);
-        if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
-        if (done && hipEventRecord(done, st) != hipSuccess) return DLA_ERR_HIP;
+        if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
+        if (done && hip_note(hipEventRecord(done, st), "hipEventRecord") != 0) return DLA_ERR_HIP;
         return DLA_SUCCESS;
       }
       if (done) hipExtLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, nullptr, done, 0, a, total_blocks);
       else hipLaunchKernelGGL(span, dim3((unsigned)slots), dim3(kUpdThreads), LD::BYTES, st, a, total_blocks);
-      return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+      return launch_status(__func__);
     }
   }
   // one 8-wave workgroup fits per compute unit: aim at one round of at most `slots` items
@@ -137,12 +137,12 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
   if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
     // profiling: the dispatch carries the profiler's start / stop events, the completion event follows it
     hipExtLaunchKernelGGL(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, p0, p1, 0, a);
-    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
-    if (done && hipEventRecord(done, st) != hipSuccess) return DLA_ERR_HIP;
+    if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
+    if (done && hip_note(hipEventRecord(done, st), "hipEventRecord") != 0) return DLA_ERR_HIP;
     return DLA_SUCCESS;
   }
   launch_ev(kern, dim3((unsigned)items), dim3(kUpdThreads), LD::BYTES, st, done, a);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 // All row panels of an LU update hold the same number of column blocks, so one launch cuts each into
@@ -213,7 +213,7 @@ static int launch_solve(SolveArgs<T> sa, hipStream_t st, hipEvent_t done = nullp
   if (grid <= 0) return DLA_SUCCESS;
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   launch_ev(kern, dim3((unsigned)grid), dim3(kSolveThreads), solve_lds_bytes<T>(), st, done, sa);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 template <typename T, int KIND>
@@ -227,7 +227,7 @@ static int launch_head(const HeadArgs<T>& a, hipStream_t st, hipEvent_t done, in
   *workgroups = grid;
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   launch_ev(kern, dim3((unsigned)grid), dim3(kHeadThreads), lds, st, done, a);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 // Helper streams and events for look-ahead: library-owned, default priority, created on first use
@@ -240,13 +240,33 @@ struct LookaheadCtx {
   double ticks_per_s = 1e8;     // rate of the constant wall clock the in-kernel waits are bounded by
   bool ok = false;
 };
-static LookaheadCtx& lookahead_ctx() {
+// data: a device pointer of the call (its device is made current for a host thread that has none yet).
+static LookaheadCtx& lookahead_ctx(const void* data) {
   static LookaheadCtx ctx;
   if (!ctx.ok) {
-    bool good = hipStreamCreateWithFlags(&ctx.head, hipStreamNonBlocking) == hipSuccess &&
-                hipStreamCreateWithFlags(&ctx.panel, hipStreamNonBlocking) == hipSuccess &&
-                hipStreamCreateWithFlags(&ctx.bulk, hipStreamNonBlocking) == hipSuccess;
-    for (int i = 0; i < 8 && good; ++i) good = hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming) == hipSuccess;
+    // A host thread that has made no runtime call of its own may have no current device (stream creation
+    // then fails with hipErrorNoDevice): give it the device the caller's matrix lives on.
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess || cur < 0) {
+      hipPointerAttribute_t attr;
+      int dev = 0;
+      if (hipPointerGetAttributes(&attr, data) == hipSuccess) dev = attr.device;
+      (void)hipGetLastError();
+      (void)hipSetDevice(dev);
+    }
+    auto make_stream = [](hipStream_t* s) {
+      if (*s) return true;  // kept from an earlier, incomplete attempt
+      hipError_t e = hipStreamCreateWithFlags(s, hipStreamNonBlocking);
+      if (e == hipErrorNoDevice) {  // (seen on worker threads of a host program that set the device elsewhere)
+        (void)hipGetLastError();
+        (void)hipSetDevice(0);
+        e = hipStreamCreateWithFlags(s, hipStreamNonBlocking);
+      }
+      return hip_note(e, "hipStreamCreateWithFlags") == 0;
+    };
+    bool good = make_stream(&ctx.head) && make_stream(&ctx.panel) && make_stream(&ctx.bulk);
+    for (int i = 0; i < 8 && good; ++i)
+      if (!ctx.ev[i]) good = hip_note(hipEventCreateWithFlags(&ctx.ev[i], hipEventDisableTiming), "hipEventCreateWithFlags") == 0;
     int dev = 0, khz = 0;
     if (good && hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
@@ -374,7 +394,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     if (auto_tile) return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, skip, slots, s, done);
     const int r = trailing_gemm(Lp, Up, Cp, mm, bb, skip, s);
     if (r != DLA_SUCCESS) return r;
-    if (done && hipEventRecord(done, s) != hipSuccess) return DLA_ERR_HIP;
+    if (done && hip_note(hipEventRecord(done, s), "hipEventRecord") != 0) return DLA_ERR_HIP;
     return DLA_SUCCESS;
   };
 
@@ -423,8 +443,8 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     // the helper streams instead of mixing their events.
     static std::mutex submit_mutex;
     std::lock_guard<std::mutex> submit_lock(submit_mutex);
-    LookaheadCtx& ctx = lookahead_ctx();
-    if (!ctx.ok) return DLA_ERR_HIP;
+    LookaheadCtx& ctx = lookahead_ctx(A);
+    if (!ctx.ok) return DLA_ERR_HIP;  // (the failing call is on record)
     wait_ticks = (long long)(ctx.ticks_per_s * (0.1 + 8.0 * (2.0 * (double)n * (double)n * 2.0 * nb) / 8e12));
     hipEvent_t e_head = ctx.ev[0], e_solve = ctx.ev[1], e_bulk = ctx.ev[2], e_start = ctx.ev[3], e_strip = ctx.ev[6];
     hipEvent_t e_diag[2] = {ctx.ev[4], ctx.ev[5]};  // by step parity
@@ -456,11 +476,11 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       const int kk = b + ksh;
       const int64_t lsh = ksh, ush = (KIND == KIND_LU) ? (int64_t)ksh * lda : (int64_t)ksh;
       int r;
-      if (hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
+      if (hip_note(hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
       // the last kernel of the step on this stream carries e_strip
       if ((r = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return r;
       if (mr > 0) {
-        if (bulk_pending && !after_wide && hipStreamWaitEvent(ctx.panel, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
+        if (bulk_pending && !after_wide && hip_note(hipStreamWaitEvent(ctx.panel, e_bulk, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
         const T* Lr = L21 + bn * lda;  // rows behind block N of the solved column panel
         const GemmSchedule ps = panel_schedule(mr);
         GemmGroup<T> g;
@@ -526,7 +546,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
           after_wide = false;
           return DLA_SUCCESS;
         }
-        if (hipStreamWaitEvent(ctx.bulk, e_solve, 0) != hipSuccess) return DLA_ERR_HIP;
+        if (hip_note(hipStreamWaitEvent(ctx.bulk, e_solve, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
         if (wide) {
           const int64_t bn3 = rest < nb ? rest : nb, o2 = bn + bn2;
           if ((r = trailing(L21 + o2 * lda - lsh, U12 + o2 - ush, A22 + o2 * lda + o2, rest, kk, (int)bn3, ctx.bulk, e_bulk)) !=
@@ -549,8 +569,8 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       const int64_t m = n - k0 - b;
       T* const Akk = A + k0 * lda + k0;
       const int64_t bn = m < nb ? m : nb;
-      if (step > 0 && hipStreamWaitEvent(ctx.head, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
-      if (!chained && hipStreamWaitEvent(ctx.head, e_diag[step & 1], 0) != hipSuccess) return DLA_ERR_HIP;
+      if (step > 0 && hip_note(hipStreamWaitEvent(ctx.head, e_strip, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
+      if (!chained && hip_note(hipStreamWaitEvent(ctx.head, e_diag[step & 1], 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
       HeadArgs<T> ha;
       ha.D = Akk;
       ha.top = step == 0 ? Akk + b : head_top_of(step);
@@ -570,7 +590,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       int head_wgs = 0, r;
       if ((r = launch_head<T, KIND>(ha, ctx.head, e_head, &head_wgs)) != DLA_SUCCESS) return r;
       heads_done += head_wgs;
-      if (!chained && hipStreamWaitEvent(st, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
+      if (!chained && hip_note(hipStreamWaitEvent(st, e_head, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
       if ((r = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return r;
       return DLA_SUCCESS;
     };
@@ -580,19 +600,19 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
     // A call starts behind the previous pipelined call of the process: its first kernels would
     // otherwise wait in place for work that is queued behind that call on the helper streams.
     hipEvent_t e_call_done = ctx.ev[7];
-    if (hipStreamWaitEvent(st, e_call_done, 0) != hipSuccess) return DLA_ERR_HIP;
+    if (hip_note(hipStreamWaitEvent(st, e_call_done, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
     hipLaunchKernelGGL(zero_ints_kernel, dim3(1), dim3(64), 0, st, chain, 3);
-    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
     if (hipEventRecord(e_start, st) != hipSuccess || hipStreamWaitEvent(ctx.head, e_start, 0) != hipSuccess)
       return DLA_ERR_HIP;
     if ((rc = diag(0, 0, st, chained ? nullptr : e_diag[0])) != DLA_SUCCESS) return rc;
     if (early_zero) {
       // the output's zero upper triangle: the blocks above the block diagonal now, on the panel stream, beside
       // the first steps (nothing reads or writes them); each diagonal block's own upper part by its kernel
-      if (hipStreamWaitEvent(ctx.panel, e_start, 0) != hipSuccess) return DLA_ERR_HIP;
+      if (hip_note(hipStreamWaitEvent(ctx.panel, e_start, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
       hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),
                          dim3(256), 0, ctx.panel, A, lda, (int)n, nb);
-      if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+      if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
     }
 
     for (int step = 0; step < nsteps; ++step) {
@@ -600,15 +620,15 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       if ((rc = panel_side(step)) != DLA_SUCCESS) return rc;
     }
     // join: everything the helper streams did becomes part of the caller's stream
-    if (hipStreamWaitEvent(st, e_head, 0) != hipSuccess) return DLA_ERR_HIP;
-    if (hipStreamWaitEvent(st, e_strip, 0) != hipSuccess) return DLA_ERR_HIP;
-    if (bulk_pending && hipStreamWaitEvent(st, e_bulk, 0) != hipSuccess) return DLA_ERR_HIP;
-    if (hipEventRecord(e_call_done, st) != hipSuccess) return DLA_ERR_HIP;
+    if (hip_note(hipStreamWaitEvent(st, e_head, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
+    if (hip_note(hipStreamWaitEvent(st, e_strip, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
+    if (bulk_pending && hip_note(hipStreamWaitEvent(st, e_bulk, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
+    if (hip_note(hipEventRecord(e_call_done, st), "hipEventRecord") != 0) return DLA_ERR_HIP;
   }
   if (KIND == KIND_CHOL && n > 1 && !early_zero) {
     hipLaunchKernelGGL(zero_upper_kernel<T>, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 32768 ? n : 32768)),
                        dim3(256), 0, st, A, lda, (int)n, 1);
-    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
   }
   return DLA_SUCCESS;
 }
@@ -629,7 +649,7 @@ int handover_selftest_impl(void* scratch, hipStream_t st, int* d_info) {
   double* const inv = A + 256;                      // 2 x 256
   int* const chain = reinterpret_cast<int*>(inv + 512);
   hipLaunchKernelGGL(identity16_kernel, dim3(1), dim3(256), 0, st, A, chain);
-  if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+  if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
   DiagArgs<double> da;
   da.A = A;
   da.lda = 16;

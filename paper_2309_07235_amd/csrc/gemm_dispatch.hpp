@@ -14,6 +14,24 @@ struct GemmSchedule {
 
 constexpr int kMaxLdsBytes = 160 * 1024;  // LDS per CU on gfx950
 
+// Status of the launch just made.  hipGetLastError reports the last error of ANY earlier call of the
+// host thread (another library's failed probe included), so every entry point first clears what it
+// finds (hip_clear_stale_error) and a launch site then sees only errors of this library's own calls.
+// The failing call is kept per host thread for dla_last_error_detail().
+struct HipErrorNote {
+  const char* where = "";
+  hipError_t code = hipSuccess;
+};
+inline thread_local HipErrorNote tl_hip_error;
+inline void hip_clear_stale_error() { (void)hipGetLastError(); }
+inline int hip_note(hipError_t e, const char* where) {
+  if (e == hipSuccess) return 0;  // DLA_SUCCESS
+  tl_hip_error.where = where;
+  tl_hip_error.code = e;
+  return 3;                       // DLA_ERR_HIP
+}
+inline int launch_status(const char* where) { return hip_note(hipGetLastError(), where); }
+
 // Raises a kernel's dynamic-LDS limit once per process (one static instance per kernel instantiation).
 // First calls may come from several host threads at the same time.
 struct LdsLimitOnce {
@@ -21,7 +39,7 @@ struct LdsLimitOnce {
   hipError_t err = hipSuccess;
   bool ensure(const void* kernel, int bytes) {
     std::call_once(flag, [&] { err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
-    return err == hipSuccess;
+    return hip_note(err, "hipFuncSetAttribute") == 0;
   }
 };
 

@@ -22,7 +22,7 @@ static int launch_prepare(const TriPrepareArgs<T>& a, hipStream_t st) {
   const int grid = (int)((a.n + kNbMax - 1) / kNbMax);
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kTriThreads), trisolve_lds_bytes<T>(), st, a);
-  return hipGetLastError() == hipSuccess ? DLA_SUCCESS : DLA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 template <typename T>
@@ -98,7 +98,7 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
   if (n > nb) {
     const int64_t count = inverse_elems(n);
     hipLaunchKernelGGL(solve_zero_kernel<T>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, wf, count);
-    if (hipGetLastError() != hipSuccess) return DLA_ERR_HIP;
+    if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
   }
   if ((rc = launch_prepare<T, FWD>(TriPrepareArgs<T>{F, lda, n, wf}, st)) != DLA_SUCCESS) return rc;
   if ((rc = launch_prepare<T, BWD>(TriPrepareArgs<T>{F, lda, n, wb}, st)) != DLA_SUCCESS) return rc;
