@@ -266,7 +266,7 @@ static int mfma_peak_impl(void* scratch, hipStream_t st, double* tflops) {
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess) return DLA_ERR_HIP;
   if (hipEventCreate(&e1) != hipSuccess) {
-    hipEventDestroy(e0);
+    (void)hipEventDestroy(e0);
     return DLA_ERR_HIP;
   }
   float best = 0.0f;
@@ -280,8 +280,8 @@ static int mfma_peak_impl(void* scratch, hipStream_t st, double* tflops) {
     ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
     if (ok && ms > 0.0f && (best == 0.0f || ms < best)) best = ms;
   }
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (!ok || best <= 0.0f) return DLA_ERR_HIP;
   const double flops = (double)kPeakGrid * 4 /*waves*/ * kPeakIters * 4 /*ILP*/ * 2048.0;  // 16*16*4*2 per MFMA
   *tflops = flops / (best * 1e-3) * 1e-12;

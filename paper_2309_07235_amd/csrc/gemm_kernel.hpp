@@ -73,7 +73,7 @@ struct RowTileLoader {
   bool ok[ITER];     // row inside the matrix
   T r[ITER][2];
 
-  __device__ inline void init(const T* __restrict__ base, int64_t ld, int tid, int rows_valid) {
+  __device__ __forceinline__ void init(const T* __restrict__ base, int64_t ld, int tid, int rows_valid) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
@@ -84,7 +84,7 @@ struct RowTileLoader {
     }
   }
   // full slab of an interior tile
-  __device__ inline void load_full(int k0) {
+  __device__ __forceinline__ void load_full(int k0) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       r[it][0] = p[it][k0];
@@ -94,7 +94,7 @@ struct RowTileLoader {
   // any slab of an edge tile, or the last (partial) slab: k_valid = K - k0 >= 1.
   // Loads stay unconditional (clamped k) and are NOT touched here: the mask is applied when the
   // registers are written to LDS, so the loads stay in flight while the previous slab is multiplied.
-  __device__ inline void load_edge(int k0, int k_valid, int tid) {
+  __device__ __forceinline__ void load_edge(int k0, int k_valid, int tid) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int c0 = 2 * ((tid + it * NT) % VPR), c1 = c0 + 1;
@@ -104,7 +104,7 @@ struct RowTileLoader {
   }
   // MASK: zero what lies outside the matrix (edge tile or partial slab)
   template <bool NEGATE, int STRIDE, bool MASK>
-  __device__ inline void store(T* __restrict__ s, int tid, int k_valid) const {
+  __device__ __forceinline__ void store(T* __restrict__ s, int tid, int k_valid) const {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
@@ -133,9 +133,13 @@ struct ColTileLoader {
   int64_t ld;
   int c0[ITER], c1[ITER];    // clamped column offsets
   bool ok0[ITER], ok1[ITER];
+  // a ragged tile with at least two valid columns: start of an in-bounds pair of neighbours that holds this
+  // thread's valid columns, and whether its first column sits in the second place of that pair
+  int cp[ITER];
+  bool sh[ITER];
   T r[ITER][2];
 
-  __device__ inline void init(const T* __restrict__ b, int64_t ld_, int tid, int cols_valid) {
+  __device__ __forceinline__ void init(const T* __restrict__ b, int64_t ld_, int tid, int cols_valid) {
     base = b;
     ld = ld_;
 #pragma unroll
@@ -147,18 +151,35 @@ struct ColTileLoader {
       ok1[it] = in && c + 1 < cols_valid;
       c0[it] = ok0[it] ? c : cols_valid - 1;
       c1[it] = ok1[it] ? c + 1 : cols_valid - 1;
+      cp[it] = ok1[it] ? c : (cols_valid >= 2 ? cols_valid - 2 : 0);
+      sh[it] = ok0[it] && !ok1[it];  // c is the last valid column: the pair starts one column before it
     }
   }
-  __device__ inline void load_full(int k0, int tid) {
+  // full slab of a ragged tile (cols_valid >= 2): same loads as an interior tile, at the in-bounds pairs
+  __device__ __forceinline__ void load_ragged(int k0, int tid) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-      const int kr = (tid + it * NT) / VPR;
+      const int kr = row_of(tid + it * NT);
+      const T* q = base + (int64_t)(k0 + kr) * ld + cp[it];
+      r[it][0] = q[0];
+      r[it][1] = q[1];
+    }
+  }
+  // threads beyond the tile (a tile smaller than the workgroup) re-read its last row
+  static __device__ __forceinline__ int row_of(int idx) {
+    const int kr = idx / VPR;
+    return (TOTAL % NT == 0 || kr < TK) ? kr : TK - 1;
+  }
+  __device__ __forceinline__ void load_full(int k0, int tid) {
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int kr = row_of(tid + it * NT);
       const T* q = base + (int64_t)(k0 + kr) * ld + 2 * ((tid + it * NT) % VPR);
       r[it][0] = q[0];
       r[it][1] = q[1];
     }
   }
-  __device__ inline void load_edge(int k0, int k_valid, int tid) {
+  __device__ __forceinline__ void load_edge(int k0, int k_valid, int tid) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int kr = (tid + it * NT) / VPR;
@@ -167,14 +188,15 @@ struct ColTileLoader {
       r[it][1] = q[c1[it]];
     }
   }
-  template <int STRIDE, bool MASK, bool NEGATE = false>
-  __device__ inline void store(T* __restrict__ s, int tid, int k_valid) const {
+  // PAIRS: the registers were filled by load_ragged
+  template <int STRIDE, bool MASK, bool NEGATE = false, bool PAIRS = false>
+  __device__ __forceinline__ void store(T* __restrict__ s, int tid, int k_valid) const {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int idx = tid + it * NT;
       if (TOTAL % NT == 0 || idx < TOTAL) {
         const int kr = idx / VPR, c2 = idx % VPR;
-        T x0 = r[it][0], x1 = r[it][1];
+        T x0 = (PAIRS && sh[it]) ? r[it][1] : r[it][0], x1 = r[it][1];
         if (MASK) {
           x0 = (ok0[it] && kr < k_valid) ? x0 : T(0);
           x1 = (ok1[it] && kr < k_valid) ? x1 : T(0);
@@ -281,16 +303,24 @@ gemm_kernel(const GemmGroup<T> g) {
   else la.init(Ag, lda, tid, M - m0);
   if (BT) lbt.init(Bg, ldb, tid, N - n0);
   else lbn.init(Bg, ldb, tid, N - n0);
-  // Two copies of the pipeline, chosen per slab: interior slabs (whole tile inside the matrix, whole
-  // slab inside K) load at constant offsets and store unmasked; everything else takes the clamped
-  // loads and the masked store.  Kept as separate loops so that the fast one stays free of selects.
-  auto fetch = [&](auto edge, int s) {
+  // Three copies of the pipeline, chosen per slab.  Interior slabs (whole tile inside the matrix, whole
+  // slab inside K) load at constant offsets and store unmasked.  Whole slabs of a ragged tile take the
+  // same loads at offsets that stay inside the matrix (rows clamped once per tile, columns as in-bounds
+  // pairs) and a masked store.  The last, partial slab takes loads clamped per element.  Kept as
+  // separate loops so that the fast ones stay free of per-element address arithmetic.
+  auto fetch = [&](auto kind, int s) __attribute__((always_inline)) {
     const int k0 = s * TK;
-    if constexpr (!decltype(edge)::value) {
+    constexpr int KIND_OF_SLAB = decltype(kind)::value;
+    if constexpr (KIND_OF_SLAB == 0) {
       if (AT) lat.load_full(k0, tid);
       else la.load_full(k0);
       if (BT) lbt.load_full(k0);
       else lbn.load_full(k0, tid);
+    } else if constexpr (KIND_OF_SLAB == 1) {
+      if (AT) lat.load_ragged(k0, tid);
+      else la.load_full(k0);
+      if (BT) lbt.load_full(k0);
+      else lbn.load_ragged(k0, tid);
     } else {
       if (AT) lat.load_edge(k0, K - k0, tid);
       else la.load_edge(k0, K - k0, tid);
@@ -298,20 +328,21 @@ gemm_kernel(const GemmGroup<T> g) {
       else lbn.load_edge(k0, K - k0, tid);
     }
   };
-  auto stash = [&](auto edge, int buf, int s) {  // s: the slab that sits in the registers
-    constexpr bool E = decltype(edge)::value;
+  auto stash = [&](auto kind, int buf, int s) __attribute__((always_inline)) {  // s: the slab that sits in the registers
+    constexpr bool E = decltype(kind)::value != 0;  // masked
+    constexpr bool P = decltype(kind)::value == 1;  // column pairs of a ragged tile
     T* sa = smem + buf * L::STAGE;
     T* sb = sa + L::A_PAD;
     const int kv = K - s * TK;
-    if (AT) lat.template store<L::SA, E, SUB>(sa, tid, kv);
+    if (AT) lat.template store<L::SA, E, SUB, P>(sa, tid, kv);
     else la.template store<SUB, L::SA, E>(sa, tid, kv);  // subtracting forms multiply by -A
     if (BT) lbt.template store<false, L::SB, E>(sb, tid, kv);
-    else lbn.template store<L::SB, E>(sb, tid, kv);
+    else lbn.template store<L::SB, E, false, P>(sb, tid, kv);
   };
-  // iterations [s0, s1): multiply slab s while slab s + 1 (when there is one) is fetched in mode `edge`
-  auto slabs = [&](auto edge, int s0, int s1) {
+  // iterations [s0, s1): multiply slab s while slab s + 1 (when there is one) is fetched as slabs of kind `edge`
+  auto slabs = [&](auto edge, int s0, int s1) __attribute__((always_inline)) {
     for (int s = s0; s < s1; ++s) {
-      const bool more = !decltype(edge)::value || (s + 1 < nslab);
+      const bool more = decltype(edge)::value != 2 || (s + 1 < nslab);
       if (more) fetch(edge, s + 1);
       const T* sa = smem + (s & 1) * L::STAGE;
       const T* sb = sa + L::A_PAD;
@@ -333,20 +364,29 @@ gemm_kernel(const GemmGroup<T> g) {
       lds_barrier();
     }
   };
-  using interior_t = std::integral_constant<bool, false>;
-  using edge_t = std::integral_constant<bool, true>;
-  const int nfull = full_mn ? K / TK : 0;  // leading slabs that need no mask
+  using interior_t = std::integral_constant<int, 0>;
+  using ragged_t = std::integral_constant<int, 1>;
+  using edge_t = std::integral_constant<int, 2>;
+  // a ragged tile can load whole slabs pairwise when its operands with contiguous columns have two valid ones
+  const bool pairs_ok = (!AT || M - m0 >= 2) && (BT || N - n0 >= 2);
+  const int nfull = (full_mn || pairs_ok) ? K / TK : 0;  // leading slabs that are whole
 
   if (nfull > 0) {
-    fetch(interior_t{}, 0);
-    stash(interior_t{}, 0, 0);
+    if (full_mn) {
+      fetch(interior_t{}, 0);
+      stash(interior_t{}, 0, 0);
+    } else {
+      fetch(ragged_t{}, 0);
+      stash(ragged_t{}, 0, 0);
+    }
   } else if (nslab > 0) {
     fetch(edge_t{}, 0);
     stash(edge_t{}, 0, 0);
   }
   lds_barrier();
-  const int split = nfull > 0 ? nfull - 1 : 0;  // iterations below it prefetch an interior slab
-  slabs(interior_t{}, 0, split);
+  const int split = nfull > 0 ? nfull - 1 : 0;  // iterations below it prefetch a whole slab
+  if (full_mn) slabs(interior_t{}, 0, split);
+  else slabs(ragged_t{}, 0, split);
   slabs(edge_t{}, split, nslab);
 
   // ---- store ---------------------------------------------------------------------
