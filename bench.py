@@ -24,10 +24,12 @@ sys.path.insert(0, ROOT)
 N_FACTOR = 4000
 PEAK_F64_MFMA_TFLOPS = 78.6   # MI355X published dense fp64 matrix peak
 METRIC = "fp64 GFLOP/s and % of MFMA fp64 peak for LU/Cholesky/3mm at N=4000"
-# HBM bytes per launch of the bulk update kernel (fetch + write), from the two rocprofv3 --pmc passes
-# summarised in profiles/update_kernel_hbm_traffic_n4000.txt (counter readings scaled by the same
-# counters' readings for a device copy of known size).  None until measured.
-UPDATE_TRAFFIC_BYTES_PER_LAUNCH = 67239 * 1024
+# HBM bytes per launch of the bulk update kernel (fetch + write) come from the summary of the two rocprofv3
+# --pmc passes that `python -m paper_2309_07235_amd.profile_summary traffic` writes (counter readings scaled
+# by the same counters' readings for a device copy of known size); null when no summary for this N is there.
+def update_traffic_bytes_per_launch(n):
+    from paper_2309_07235_amd.profile_summary import read_traffic
+    return read_traffic(os.path.join(ROOT, "profiles", f"update_kernel_hbm_traffic_n{n}.txt"), n)
 
 
 def update_algorithmic_bytes(n, nb=128, lower=False, defer_min_rows=0):
@@ -242,7 +244,7 @@ def main(argv=None) -> int:
         "pct_of_measured_fp64_mfma_peak": round(gflops * 1e-3 / measured_peak * 100, 2),
         "kernels": kernels,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_F64_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": UPDATE_TRAFFIC_BYTES_PER_LAUNCH if n == N_FACTOR else None,
+                     "frac": round(achieved / PEAK_F64_MFMA_TFLOPS, 4), "traffic": update_traffic_bytes_per_launch(n),
                      "kernel": "update_kernel (bulk trailing update of lu_factor and cholesky_factor, all launches)",
                      "launches": upd_launches, "avg_launch_ms": round(upd_ms / max(upd_launches, 1), 5),
                      "flops_per_launch": round(upd_fl / max(upd_launches, 1), 1),
