@@ -136,6 +136,17 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   constexpr int TPK = kUpdThreads / KMAX;             // LU: threads that share one k-row of the block
   static_assert(TPK * BPT == kUpdCols && BPT <= 16 && 16 % BPT == 0, "right-operand staging");
   T bst[BPT];
+  // A block that lies inside the matrix with the full depth b = KMAX: no conditions, and every address is a
+  // pointer that is uniform over the workgroup (scalar registers) plus one per-lane byte offset that never
+  // changes, so the loads in flight do not each hold a 64-bit address in vector registers.
+  const uint32_t boff = !LOWER ? (uint32_t)(((int64_t)(tid / TPK) * ld + (tid % TPK) * BPT) * (int64_t)sizeof(T))
+                               : (uint32_t)(((int64_t)(tid % kUpdCols) * ld + (tid / kUpdCols) * BPT) * (int64_t)sizeof(T));
+  auto fetch_b_full = [&](int j0) __attribute__((always_inline)) {
+    const char* const base = reinterpret_cast<const char*>(!LOWER ? g.R + j0 : g.R + (int64_t)j0 * ld);
+    const T* p = reinterpret_cast<const T*>(base + boff);
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) bst[i] = p[i];
+  };
   auto fetch_b = [&](int j0) {
     if (!LOWER) {
       const int k = tid / TPK, c0 = (tid % TPK) * BPT;
@@ -188,6 +199,24 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   };
   // ---- C block of this wave: 16 rows x cols columns = NCB MFMA blocks ------------------------------
   T* const Cw = g.C + (int64_t)wrow0 * ld;
+  // (row_of(v, lane) = row_of(v, 0) + row_of(0, lane): the first part is the same for all lanes)
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  char* const Cs = reinterpret_cast<char*>(g.C + (int64_t)(row0 + wave_s * 16) * ld);
+  const uint32_t coff = (uint32_t)(((int64_t)Mfma<T>::row_of(0, lane) * ld + l15) * (int64_t)sizeof(T));
+  auto fetch_c_full = [&](acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < NCB; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        c[q][v] = *reinterpret_cast<const T*>(Cs + ((int64_t)Mfma<T>::row_of(v, 0) * ld + j0 + q * 16) * (int64_t)sizeof(T) + coff);
+  };
+  auto store_c_full = [&](const acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < NCB; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        *reinterpret_cast<T*>(Cs + ((int64_t)Mfma<T>::row_of(v, 0) * ld + j0 + q * 16) * (int64_t)sizeof(T) + coff) = c[q][v];
+  };
   auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
     if (full) {
@@ -278,9 +307,63 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
       lds_barrier();  // X
     }
   };
+  // The same block step without a condition in it, for blocks that lie inside the matrix, are not part of the
+  // excluded leading block and have two such blocks behind them: in straight-line code the compiler counts the
+  // loads in flight exactly (a C block is used two steps after its loads, behind twelve younger loads and
+  // stores), where the branches of the general form make it wait for every load before every use, which
+  // turns the prefetches into round trips.  Both forms keep the same two barriers per step and the same LDS
+  // protocol, so the waves of a workgroup may take different forms in the same step.
+  const int grp_s = __builtin_amdgcn_readfirstlane(grp);
+  auto fast_step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_, int b_) __attribute__((always_inline)) {
+    const int jnn = jc_ + 2 * col_step;
+    multiply(cur, b_);
+    lds_barrier();  // Y
+    stash_b(b_ ^ 1);
+    fetch_b_full(jnn);
+    store_c_full(cur, jc_);
+    fetch_c_full(tgt, jnn);
+    lds_barrier();  // X
+  };
+  auto fast_step1 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp_, int jc_, int b_) __attribute__((always_inline)) {
+    const int jnn = jc_ + 2 * col_step;
+    stash_b(b_ ^ 1);
+    fetch_b_full(jnn);
+    store_c_full(tgt, jp_);
+    fetch_c_full(tgt, jnn);
+    lds_barrier();  // Y
+    multiply(cur, b_);
+    lds_barrier();  // X
+  };
+  // (measured: it pays for the fp64 LU update; the lower-triangular and the fp32 forms keep the general steps)
+  constexpr bool kPlainSteps = !LOWER && sizeof(T) == 8;
+  const bool wave_plain = kPlainSteps && (wrow0 + 16 <= m) && (b == KMAX) && ld * (int64_t)(KMAX * sizeof(T)) < ((int64_t)1 << 32);
+  auto three_plain_steps = [&](int jp_, int jc_) {  // steps at jc_, jc_ + col_step, jc_ + 2 col_step and their prefetches
+    return wave_plain && (jc_ + 4 * col_step + kUpdCols <= col_end) && (wrow0 >= g.skip || jp_ >= g.skip);
+  };
   int jp = col_begin, jc = col_begin;
   bool first = true;
   for (;;) {
+    if (kPlainSteps && !first) {
+      if (grp_s == 0) {
+        while (__builtin_amdgcn_readfirstlane((int)three_plain_steps(jp, jc))) {
+          fast_step0(c0, c2, jc, buf);
+          fast_step0(c1, c0, jc + col_step, buf ^ 1);
+          fast_step0(c2, c1, jc + 2 * col_step, buf);
+          buf ^= 1;
+          jp = jc + 2 * col_step;
+          jc += 3 * col_step;
+        }
+      } else {
+        while (__builtin_amdgcn_readfirstlane((int)three_plain_steps(jp, jc))) {
+          fast_step1(c0, c2, jp, jc, buf);
+          fast_step1(c1, c0, jc, jc + col_step, buf ^ 1);
+          fast_step1(c2, c1, jc + col_step, jc + 2 * col_step, buf);
+          buf ^= 1;
+          jp = jc + 2 * col_step;
+          jc += 3 * col_step;
+        }
+      }
+    }
     block_step(c0, c2, jp, jc, first, buf);
     buf ^= 1;
     first = false;
