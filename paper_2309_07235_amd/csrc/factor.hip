@@ -85,7 +85,7 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
                               hipStream_t st, hipEvent_t done) {
   constexpr bool LOWER = (KIND == KIND_CHOL);
   constexpr int COLS = NCB * 16;
-  auto kern = update_kernel<T, LOWER, NCB, KMAX>;
+  void (*kern)(UpdateArgs<T>) = update_kernel<T, LOWER, NCB, KMAX>;
   using LD = UpdateLds<T, LOWER, NCB, KMAX>;
   static LdsLimitOnce lds_limit;
   if (!lds_limit.ensure(reinterpret_cast<const void*>(kern), LD::BYTES)) return DLA_ERR_HIP;
@@ -133,6 +133,14 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
   a.items = items;
+  // long work items of the fp64 LU update: the instantiation whose steady-state steps carry no condition
+  if constexpr (!LOWER && sizeof(T) == 8) {
+    if (a.bpi >= kUpdPlainMinBlocks) {
+      kern = update_kernel<T, LOWER, NCB, KMAX, true>;
+      static LdsLimitOnce plain_lds_limit;
+      if (!plain_lds_limit.ensure(reinterpret_cast<const void*>(kern), LD::BYTES)) return DLA_ERR_HIP;
+    }
+  }
   hipEvent_t p0 = nullptr, p1 = nullptr;
   if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {
     // profiling: the dispatch carries the profiler's start / stop events, the completion event follows it

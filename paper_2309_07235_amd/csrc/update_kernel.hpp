@@ -42,6 +42,7 @@ namespace dla {
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
 constexpr int kUpdThreads = 512;
 constexpr int kUpdKMax = 128;   // largest block size b (depth of one panel)
+constexpr int kUpdPlainMinBlocks = 36;  // work items of at least this many column blocks take the kernel with condition-free steps
 
 template <typename T>
 struct UpdateArgs {
@@ -80,7 +81,7 @@ __host__ __device__ inline int update_items_of_panel(int p, int m, int bpi, bool
 
 // One segment of a work item: the row panel `panel` against the column blocks col_begin,
 // col_begin + col_step, ... whose first column lies below col_end.
-template <typename T, bool LOWER, int NCB, int KMAX>
+template <typename T, bool LOWER, int NCB, int KMAX, bool PLAIN = false>
 __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const smem, const int panel, const int col_begin,
                                                const int col_step, const int col_end) {
   using acc_t = typename Mfma<T>::acc_t;
@@ -334,8 +335,10 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     multiply(cur, b_);
     lds_barrier();  // X
   };
-  // (measured: it pays for the fp64 LU update; the lower-triangular and the fp32 forms keep the general steps)
-  constexpr bool kPlainSteps = !LOWER && sizeof(T) == 8;
+  // PLAIN: a second instantiation of the kernel; the one without it is the general steps alone (the host takes
+  // it for work items of fewer than kUpdPlainMinBlocks blocks, whose share of general steps is large, and for the
+  // lower-triangular and fp32 forms: measured)
+  constexpr bool kPlainSteps = PLAIN;
   const bool wave_plain = kPlainSteps && (wrow0 + 16 <= m) && (b == KMAX) && ld * (int64_t)(KMAX * sizeof(T)) < ((int64_t)1 << 32);
   auto three_plain_steps = [&](int jp_, int jc_) {  // steps at jc_, jc_ + col_step, jc_ + 2 col_step and their prefetches
     return wave_plain && (jc_ + 4 * col_step + kUpdCols <= col_end) && (wrow0 >= g.skip || jp_ >= g.skip);
@@ -392,7 +395,7 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   }
 }
 
-template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax>
+template <typename T, bool LOWER, int NCB, int KMAX = kUpdKMax, bool PLAIN = false>
 __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T> g) {
   static_assert(KMAX % 64 == 0 && kUpdThreads % KMAX == 0, "depth");
   constexpr int kUpdCols = NCB * 16;  // columns per iteration
@@ -423,7 +426,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
   (void)nblocks;
   if (col_begin >= col_end) return;  // uniform
 
-  update_segment<T, LOWER, NCB, KMAX>(g, smem, panel, col_begin, col_step, col_end);
+  update_segment<T, LOWER, NCB, KMAX, PLAIN>(g, smem, panel, col_begin, col_step, col_end);
 }
 
 // The same update with work items of exactly equal size for the lower-triangular form, whose row
