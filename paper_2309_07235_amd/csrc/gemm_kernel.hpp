@@ -37,7 +37,7 @@ struct GemmProblem {
   int64_t ldc2;
 };
 
-constexpr int kMaxGroup = 5;  // products one launch can carry
+constexpr int kMaxGroup = 16;  // products one launch can carry
 
 template <typename T>
 struct GemmGroup {
