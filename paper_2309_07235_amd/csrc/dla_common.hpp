@@ -11,6 +11,8 @@ typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef double double2_t __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 // One 16x16x4 MFMA step  D(16x16) = A(16x4) * B(4x16) + C  on a 64-lane wavefront.
 // Operand layouts (checked against the hardware with a register-dump probe):

@@ -105,7 +105,7 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
   if constexpr (LOWER) {
     // a large trapezoid: work items of equal size that cross row panels (see update_span_kernel)
     if (m >= kSpanMinRows && total_blocks >= 8 * (int64_t)slots) {
-      auto span = update_span_kernel<T, NCB, KMAX>;
+      auto span = update_span_kernel<T, NCB, KMAX, kUpdPlainForm<T, true>>;
       static LdsLimitOnce span_lds_limit;
       if (!span_lds_limit.ensure(reinterpret_cast<const void*>(span), LD::BYTES)) return DLA_ERR_HIP;
       a.bpi = 1;
@@ -133,8 +133,8 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
   a.items = items;
-  // long work items of the fp64 LU update: the instantiation whose steady-state steps carry no condition
-  if constexpr (!LOWER && sizeof(T) == 8) {
+  // work items of some length: the instantiation whose steady-state steps carry no condition
+  if constexpr (kUpdPlainForm<T, LOWER>) {
     if (a.bpi >= kUpdPlainMinBlocks) {
       kern = update_kernel<T, LOWER, NCB, KMAX, true>;
       static LdsLimitOnce plain_lds_limit;

@@ -42,7 +42,10 @@ namespace dla {
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
 constexpr int kUpdThreads = 512;
 constexpr int kUpdKMax = 128;   // largest block size b (depth of one panel)
-constexpr int kUpdPlainMinBlocks = 36;  // work items of at least this many column blocks take the kernel with condition-free steps
+constexpr int kUpdPlainMinBlocks = 12;  // work items of at least this many column blocks take the kernel with condition-free steps
+// ... for these forms (measured: the fp32 lower-triangular update is as fast or faster without them)
+template <typename T, bool LOWER>
+constexpr bool kUpdPlainForm = sizeof(T) == 8 || !LOWER;
 
 template <typename T>
 struct UpdateArgs {
@@ -138,15 +141,41 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   static_assert(TPK * BPT == kUpdCols && BPT <= 16 && 16 % BPT == 0, "right-operand staging");
   T bst[BPT];
   // A block that lies inside the matrix with the full depth b = KMAX: no conditions, and every address is a
-  // pointer that is uniform over the workgroup (scalar registers) plus one per-lane byte offset that never
-  // changes, so the loads in flight do not each hold a 64-bit address in vector registers.
+  // base that is uniform over the wave (scalar registers) plus one per-lane byte offset that never changes.
   const uint32_t boff = !LOWER ? (uint32_t)(((int64_t)(tid / TPK) * ld + (tid % TPK) * BPT) * (int64_t)sizeof(T))
                                : (uint32_t)(((int64_t)(tid % kUpdCols) * ld + (tid / kUpdCols) * BPT) * (int64_t)sizeof(T));
+  // Those loads and stores are buffer instructions: a resource in scalar registers (base and extent), a scalar
+  // byte offset per instruction and the constant per-lane offset.  No 64-bit address is ever formed in vector
+  // registers, which is what the register allocation of the steady-state loop needs: with flat addresses the
+  // loop spilled address pairs (and a reload brings a wait for every load in flight back) or reused
+  // accumulator registers whose stores were still reading them.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  char* const Cs = reinterpret_cast<char*>(g.C + (int64_t)(row0 + wave_s * 16) * ld);  // this wave's 16 rows of C
+  const int64_t ext_c = ((int64_t)15 * ld + mc) * (int64_t)sizeof(T);
+  const int64_t ext_r = (!LOWER ? (int64_t)(KMAX - 1) * ld + mc : (int64_t)(m - 1) * ld + KMAX) * (int64_t)sizeof(T);
+  const bool ext_fit = ext_c < ((int64_t)1 << 32) && ext_r < ((int64_t)1 << 32);
+  // (flags: raw 32-bit data format of gfx9-family buffer resources, no swizzle, stride 0: offsets are plain bytes)
+  const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, ext_fit ? (int)(uint32_t)ext_c : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_r =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(g.R), 0, ext_fit ? (int)(uint32_t)ext_r : 0, 0x00020000);
   auto fetch_b_full = [&](int j0) __attribute__((always_inline)) {
-    const char* const base = reinterpret_cast<const char*>(!LOWER ? g.R + j0 : g.R + (int64_t)j0 * ld);
-    const T* p = reinterpret_cast<const T*>(base + boff);
+    const uint32_t so = !LOWER ? (uint32_t)j0 * (uint32_t)sizeof(T) : (uint32_t)j0 * (uint32_t)ld * (uint32_t)sizeof(T);
+    constexpr int PER = 16 / (int)sizeof(T);  // elements per 16-byte load
 #pragma unroll
-    for (int i = 0; i < BPT; ++i) bst[i] = p[i];
+    for (int i = 0; i < BPT; i += PER) {
+      const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_r, (int)(boff + i * (int)sizeof(T)), (int)so, 0);
+      if constexpr (sizeof(T) == 8) {
+        const double2_t d = __builtin_bit_cast(double2_t, w);
+        bst[i] = d[0];
+        bst[i + 1] = d[1];
+      } else {
+        const float4_t d = __builtin_bit_cast(float4_t, w);
+        bst[i] = d[0];
+        bst[i + 1] = d[1];
+        bst[i + 2] = d[2];
+        bst[i + 3] = d[3];
+      }
+    }
   };
   auto fetch_b = [&](int j0) {
     if (!LOWER) {
@@ -201,22 +230,26 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // ---- C block of this wave: 16 rows x cols columns = NCB MFMA blocks ------------------------------
   T* const Cw = g.C + (int64_t)wrow0 * ld;
   // (row_of(v, lane) = row_of(v, 0) + row_of(0, lane): the first part is the same for all lanes)
-  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-  char* const Cs = reinterpret_cast<char*>(g.C + (int64_t)(row0 + wave_s * 16) * ld);
   const uint32_t coff = (uint32_t)(((int64_t)Mfma<T>::row_of(0, lane) * ld + l15) * (int64_t)sizeof(T));
   auto fetch_c_full = [&](acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
 #pragma unroll
     for (int q = 0; q < NCB; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        c[q][v] = *reinterpret_cast<const T*>(Cs + ((int64_t)Mfma<T>::row_of(v, 0) * ld + j0 + q * 16) * (int64_t)sizeof(T) + coff);
+      for (int v = 0; v < 4; ++v) {
+        const uint32_t so = ((uint32_t)Mfma<T>::row_of(v, 0) * (uint32_t)ld + (uint32_t)(j0 + q * 16)) * (uint32_t)sizeof(T);
+        if constexpr (sizeof(T) == 8) c[q][v] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs_c, (int)coff, (int)so, 0));
+        else c[q][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_c, (int)coff, (int)so, 0));
+      }
   };
   auto store_c_full = [&](const acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
 #pragma unroll
     for (int q = 0; q < NCB; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        *reinterpret_cast<T*>(Cs + ((int64_t)Mfma<T>::row_of(v, 0) * ld + j0 + q * 16) * (int64_t)sizeof(T) + coff) = c[q][v];
+      for (int v = 0; v < 4; ++v) {
+        const uint32_t so = ((uint32_t)Mfma<T>::row_of(v, 0) * (uint32_t)ld + (uint32_t)(j0 + q * 16)) * (uint32_t)sizeof(T);
+        if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, (double)c[q][v]), rs_c, (int)coff, (int)so, 0);
+        else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, (float)c[q][v]), rs_c, (int)coff, (int)so, 0);
+      }
   };
   auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
@@ -313,10 +346,15 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // loads in flight exactly (a C block is used two steps after its loads, behind twelve younger loads and
   // stores), where the branches of the general form make it wait for every load before every use, which
   // turns the prefetches into round trips.  Both forms keep the same two barriers per step and the same LDS
-  // protocol, so the waves of a workgroup may take different forms in the same step.
+  // protocol, so the waves of a workgroup may take different forms in the same step.  (Barrier Y protects no
+  // data, it keeps the wave groups in anti-phase; without it the large updates are 3-10 % slower: measured.)
   const int grp_s = __builtin_amdgcn_readfirstlane(grp);
-  auto fast_step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_, int b_) __attribute__((always_inline)) {
-    const int jnn = jc_ + 2 * col_step;
+  const int col_step_s = __builtin_amdgcn_readfirstlane(col_step);
+  // (the column positions are the same in every lane; said explicitly, so that the offsets of the buffer
+  // instructions are computed in scalar registers)
+  auto fast_step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_v, int b_) __attribute__((always_inline)) {
+    const int jc_ = __builtin_amdgcn_readfirstlane(jc_v);
+    const int jnn = jc_ + 2 * col_step_s;
     multiply(cur, b_);
     lds_barrier();  // Y
     stash_b(b_ ^ 1);
@@ -325,8 +363,9 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     fetch_c_full(tgt, jnn);
     lds_barrier();  // X
   };
-  auto fast_step1 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp_, int jc_, int b_) __attribute__((always_inline)) {
-    const int jnn = jc_ + 2 * col_step;
+  auto fast_step1 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp_v, int jc_v, int b_) __attribute__((always_inline)) {
+    const int jp_ = __builtin_amdgcn_readfirstlane(jp_v), jc_ = __builtin_amdgcn_readfirstlane(jc_v);
+    const int jnn = jc_ + 2 * col_step_s;
     stash_b(b_ ^ 1);
     fetch_b_full(jnn);
     store_c_full(tgt, jp_);
@@ -337,9 +376,9 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   };
   // PLAIN: a second instantiation of the kernel; the one without it is the general steps alone (the host takes
   // it for work items of fewer than kUpdPlainMinBlocks blocks, whose share of general steps is large, and for the
-  // lower-triangular and fp32 forms: measured)
+  // fp32 lower-triangular form: measured)
   constexpr bool kPlainSteps = PLAIN;
-  const bool wave_plain = kPlainSteps && (wrow0 + 16 <= m) && (b == KMAX) && ld * (int64_t)(KMAX * sizeof(T)) < ((int64_t)1 << 32);
+  const bool wave_plain = kPlainSteps && (wrow0 + 16 <= m) && (b == KMAX) && ext_fit;
   auto three_plain_steps = [&](int jp_, int jc_) {  // steps at jc_, jc_ + col_step, jc_ + 2 col_step and their prefetches
     return wave_plain && (jc_ + 4 * col_step + kUpdCols <= col_end) && (wrow0 >= g.skip || jp_ >= g.skip);
   };
@@ -434,7 +473,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_kernel(const UpdateArgs<T>
 // panel, are cut into gridDim.x equal runs, and a workgroup walks its run, reloading the left panel
 // where the run crosses into the next row panel.  (Per-panel items, as above, leave a quarter of the
 // compute units idle on a large trapezoid: a small panel's item is a fraction of a large panel's.)
-template <typename T, int NCB, int KMAX = kUpdKMax>
+template <typename T, int NCB, int KMAX = kUpdKMax, bool PLAIN = false>
 __global__ void __launch_bounds__(kUpdThreads) update_span_kernel(const UpdateArgs<T> g, const int64_t total_blocks) {
   constexpr int kUpdCols = NCB * 16;
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -454,7 +493,7 @@ __global__ void __launch_bounds__(kUpdThreads) update_span_kernel(const UpdateAr
     const int64_t take = left < here - lo ? left : here - lo;
     const int width = (panel + 1) * kUpdRows < m ? (panel + 1) * kUpdRows : m;
     const int end = (int)(lo + take) * kUpdCols;
-    update_segment<T, true, NCB, KMAX>(g, smem, panel, (int)lo * kUpdCols, kUpdCols, end < width ? end : width);
+    update_segment<T, true, NCB, KMAX, PLAIN>(g, smem, panel, (int)lo * kUpdCols, kUpdCols, end < width ? end : width);
     lds_barrier();  // the next segment restages the left panel through the same memory
     left -= take;
     lo = 0;
