@@ -133,13 +133,11 @@ static int launch_update_rows(const T* L, const T* R, T* C, int64_t ld, int64_t 
     ++a.bpi;  // rounding up per panel overshot the slot count
   }
   a.items = items;
-  // work items of some length: the instantiation whose steady-state steps carry no condition
+  // the instantiation whose work items run without a condition in their steps where they lie inside the matrix
   if constexpr (kUpdPlainForm<T, LOWER>) {
-    if (a.bpi >= kUpdPlainMinBlocks) {
-      kern = update_kernel<T, LOWER, NCB, KMAX, true>;
-      static LdsLimitOnce plain_lds_limit;
-      if (!plain_lds_limit.ensure(reinterpret_cast<const void*>(kern), LD::BYTES)) return DLA_ERR_HIP;
-    }
+    kern = update_kernel<T, LOWER, NCB, KMAX, true>;
+    static LdsLimitOnce plain_lds_limit;
+    if (!plain_lds_limit.ensure(reinterpret_cast<const void*>(kern), LD::BYTES)) return DLA_ERR_HIP;
   }
   hipEvent_t p0 = nullptr, p1 = nullptr;
   if (profile_kernel_events(PHASE_UPDATE, flops, &p0, &p1)) {

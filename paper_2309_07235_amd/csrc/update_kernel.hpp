@@ -42,10 +42,9 @@ namespace dla {
 constexpr int kUpdRows = 128;   // rows per workgroup (8 waves x 16 rows)
 constexpr int kUpdThreads = 512;
 constexpr int kUpdKMax = 128;   // largest block size b (depth of one panel)
-constexpr int kUpdPlainMinBlocks = 12;  // work items of at least this many column blocks take the kernel with condition-free steps
-// ... for these forms (measured: the fp32 lower-triangular update is as fast or faster without them)
+// the forms that take the kernel instantiation with condition-free work items
 template <typename T, bool LOWER>
-constexpr bool kUpdPlainForm = sizeof(T) == 8 || !LOWER;
+constexpr bool kUpdPlainForm = true;
 
 template <typename T>
 struct UpdateArgs {
@@ -151,19 +150,25 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // accumulator registers whose stores were still reading them.
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   char* const Cs = reinterpret_cast<char*>(g.C + (int64_t)(row0 + wave_s * 16) * ld);  // this wave's 16 rows of C
+  // Offsets at or above kOob lie outside every resource used here (extents stay below 2^31 bytes): the hardware
+  // returns zero for such a load and drops such a store, which is how a step switches off a prefetch or a store
+  // that has no block to go to without a branch in the instruction stream.
+  constexpr uint32_t kOob = 0x80000000u;
+  constexpr int kRsrcFlags = 0x00020000;  // raw 32-bit data format of gfx9-family resources, no swizzle: offsets are plain bytes
   const int64_t ext_c = ((int64_t)15 * ld + mc) * (int64_t)sizeof(T);
-  const int64_t ext_r = (!LOWER ? (int64_t)(KMAX - 1) * ld + mc : (int64_t)(m - 1) * ld + KMAX) * (int64_t)sizeof(T);
-  const bool ext_fit = ext_c < ((int64_t)1 << 32) && ext_r < ((int64_t)1 << 32);
-  // (flags: raw 32-bit data format of gfx9-family buffer resources, no swizzle, stride 0: offsets are plain bytes)
-  const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, ext_fit ? (int)(uint32_t)ext_c : 0, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rs_r =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(g.R), 0, ext_fit ? (int)(uint32_t)ext_r : 0, 0x00020000);
-  auto fetch_b_full = [&](int j0) __attribute__((always_inline)) {
-    const uint32_t so = !LOWER ? (uint32_t)j0 * (uint32_t)sizeof(T) : (uint32_t)j0 * (uint32_t)ld * (uint32_t)sizeof(T);
+  // one right-operand block: LU: KMAX rows of kUpdCols columns;  lower-triangular form: kUpdCols rows of KMAX columns
+  const int64_t ext_r = (!LOWER ? (int64_t)(KMAX - 1) * ld + kUpdCols : (int64_t)(kUpdCols - 1) * ld + KMAX) * (int64_t)sizeof(T);
+  const bool ext_fit = ext_c < (int64_t)kOob && ext_r < (int64_t)kOob;
+  const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(Cs, 0, ext_fit ? (int)ext_c : 0, kRsrcFlags);
+  auto fetch_b_full = [&](int j0, bool on) __attribute__((always_inline)) {
+    // the resource starts at the block, so that its extent does not grow with the matrix
+    const T* const base = !LOWER ? g.R + j0 : g.R + (int64_t)j0 * ld;
+    const __amdgpu_buffer_rsrc_t rs_r = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(base), 0, ext_fit ? (int)ext_r : 0, kRsrcFlags);
+    const uint32_t vo = on ? boff : kOob;
     constexpr int PER = 16 / (int)sizeof(T);  // elements per 16-byte load
 #pragma unroll
     for (int i = 0; i < BPT; i += PER) {
-      const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_r, (int)(boff + i * (int)sizeof(T)), (int)so, 0);
+      const u32x4_t w = __builtin_amdgcn_raw_buffer_load_b128(rs_r, (int)(vo + i * (int)sizeof(T)), 0, 0);
       if constexpr (sizeof(T) == 8) {
         const double2_t d = __builtin_bit_cast(double2_t, w);
         bst[i] = d[0];
@@ -231,24 +236,26 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   T* const Cw = g.C + (int64_t)wrow0 * ld;
   // (row_of(v, lane) = row_of(v, 0) + row_of(0, lane): the first part is the same for all lanes)
   const uint32_t coff = (uint32_t)(((int64_t)Mfma<T>::row_of(0, lane) * ld + l15) * (int64_t)sizeof(T));
-  auto fetch_c_full = [&](acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
+  auto fetch_c_full = [&](acc_t (&c)[NCB], int j0, bool on) __attribute__((always_inline)) {
+    const uint32_t vo = on ? coff : kOob;
 #pragma unroll
     for (int q = 0; q < NCB; ++q)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const uint32_t so = ((uint32_t)Mfma<T>::row_of(v, 0) * (uint32_t)ld + (uint32_t)(j0 + q * 16)) * (uint32_t)sizeof(T);
-        if constexpr (sizeof(T) == 8) c[q][v] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs_c, (int)coff, (int)so, 0));
-        else c[q][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_c, (int)coff, (int)so, 0));
+        if constexpr (sizeof(T) == 8) c[q][v] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rs_c, (int)vo, (int)so, 0));
+        else c[q][v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_c, (int)vo, (int)so, 0));
       }
   };
-  auto store_c_full = [&](const acc_t (&c)[NCB], int j0) __attribute__((always_inline)) {
+  auto store_c_full = [&](const acc_t (&c)[NCB], int j0, bool on) __attribute__((always_inline)) {
+    const uint32_t vo = on ? coff : kOob;
 #pragma unroll
     for (int q = 0; q < NCB; ++q)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const uint32_t so = ((uint32_t)Mfma<T>::row_of(v, 0) * (uint32_t)ld + (uint32_t)(j0 + q * 16)) * (uint32_t)sizeof(T);
-        if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, (double)c[q][v]), rs_c, (int)coff, (int)so, 0);
-        else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, (float)c[q][v]), rs_c, (int)coff, (int)so, 0);
+        if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, (double)c[q][v]), rs_c, (int)vo, (int)so, 0);
+        else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, (float)c[q][v]), rs_c, (int)vo, (int)so, 0);
       }
   };
   auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
@@ -316,6 +323,92 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
     if (jnn < col_end) fetch_c(tgt, jnn);
   };
   acc_t c0[NCB], c1[NCB], c2[NCB];
+  // ---- the whole work item without a condition in its steps ------------------------------------------------
+  // For a wave whose rows, and a work item all of whose blocks, lie inside the matrix and outside the excluded
+  // leading block (full depth b = KMAX): in straight-line code the compiler counts the loads in flight exactly
+  // (a C block is used two steps after its loads, behind twelve younger loads and stores), where the branches
+  // of the general form make it wait for every load before every use, which turns the prefetches into round
+  // trips.  What the ends of the item need -- no store before the first block has been multiplied, no prefetch
+  // behind the last block -- is switched off through the offset (kOob), not by a branch.  The steps come three
+  // to a loop iteration (one rotation of the accumulator sets) and one or two more behind the loop.  Barriers
+  // and LDS protocol are those of the general form below, step for step, so the waves of a workgroup may take
+  // different forms.  (Barrier Y protects no data, it keeps the wave groups in anti-phase; without it the large
+  // updates are 3-10 % slower: measured.)
+  if constexpr (PLAIN) {
+    const int cb = __builtin_amdgcn_readfirstlane(col_begin), cs = __builtin_amdgcn_readfirstlane(col_step);
+    const int ce = __builtin_amdgcn_readfirstlane(col_end);
+    const int nblk = (ce - cb + cs - 1) / cs;  // blocks of this item
+    const bool item_plain = (wrow0 + 16 <= m) && (b == KMAX) && ext_fit && (cb + (nblk - 1) * cs + kUpdCols <= mc) &&
+                            (wrow0 >= g.skip || cb >= g.skip);
+    if (__builtin_amdgcn_readfirstlane((int)item_plain)) {
+      const int grp_s = __builtin_amdgcn_readfirstlane(wave >> 2);
+      auto step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_, int b_) __attribute__((always_inline)) {
+        const int jnn = jc_ + 2 * cs;
+        const bool prefetch = jnn < ce;
+        multiply(cur, b_);
+        lds_barrier();  // Y
+        stash_b(b_ ^ 1);
+        fetch_b_full(jnn, prefetch);
+        store_c_full(cur, jc_, true);
+        fetch_c_full(tgt, jnn, prefetch);
+        lds_barrier();  // X
+      };
+      auto step1 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_, int b_, bool store) __attribute__((always_inline)) {
+        const int jnn = jc_ + 2 * cs;
+        const bool prefetch = jnn < ce;
+        stash_b(b_ ^ 1);
+        fetch_b_full(jnn, prefetch);
+        store_c_full(tgt, jc_ - cs, store);  // the previous block's result
+        fetch_c_full(tgt, jnn, prefetch);
+        lds_barrier();  // Y
+        multiply(cur, b_);
+        lds_barrier();  // X
+      };
+      int jc = cb, left = nblk, bf = 0;
+      fetch_b_full(jc, true);
+      fetch_c_full(c0, jc, true);
+      stash_b(0);
+      fetch_b_full(jc + cs, left > 1);
+      fetch_c_full(c1, jc + cs, left > 1);
+      lds_barrier();
+      if (grp_s == 0) {
+        while (left >= 3) {
+          step0(c0, c2, jc, bf);
+          step0(c1, c0, jc + cs, bf ^ 1);
+          step0(c2, c1, jc + 2 * cs, bf);
+          bf ^= 1;
+          jc += 3 * cs;
+          left -= 3;
+        }
+        if (left >= 1) step0(c0, c2, jc, bf);
+        if (left == 2) step0(c1, c0, jc + cs, bf ^ 1);
+      } else {
+        bool started = false;
+        while (left >= 3) {
+          step1(c0, c2, jc, bf, started);
+          step1(c1, c0, jc + cs, bf ^ 1, true);
+          step1(c2, c1, jc + 2 * cs, bf, true);
+          started = true;
+          bf ^= 1;
+          jc += 3 * cs;
+          left -= 3;
+        }
+        if (left == 0) {
+          store_c_full(c2, jc - cs, true);
+        } else {
+          step1(c0, c2, jc, bf, started);
+          if (left == 2) {
+            step1(c1, c0, jc + cs, bf ^ 1, true);
+            store_c_full(c1, jc + cs, true);
+          } else {
+            store_c_full(c0, jc, true);
+          }
+        }
+      }
+      return;
+    }
+  }
+  // ---- the general form ------------------------------------------------------------------------------------
   fetch_b(col_begin);
   fetch_c(c0, col_begin);
   stash_b(0);
@@ -341,71 +434,9 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
       lds_barrier();  // X
     }
   };
-  // The same block step without a condition in it, for blocks that lie inside the matrix, are not part of the
-  // excluded leading block and have two such blocks behind them: in straight-line code the compiler counts the
-  // loads in flight exactly (a C block is used two steps after its loads, behind twelve younger loads and
-  // stores), where the branches of the general form make it wait for every load before every use, which
-  // turns the prefetches into round trips.  Both forms keep the same two barriers per step and the same LDS
-  // protocol, so the waves of a workgroup may take different forms in the same step.  (Barrier Y protects no
-  // data, it keeps the wave groups in anti-phase; without it the large updates are 3-10 % slower: measured.)
-  const int grp_s = __builtin_amdgcn_readfirstlane(grp);
-  const int col_step_s = __builtin_amdgcn_readfirstlane(col_step);
-  // (the column positions are the same in every lane; said explicitly, so that the offsets of the buffer
-  // instructions are computed in scalar registers)
-  auto fast_step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_v, int b_) __attribute__((always_inline)) {
-    const int jc_ = __builtin_amdgcn_readfirstlane(jc_v);
-    const int jnn = jc_ + 2 * col_step_s;
-    multiply(cur, b_);
-    lds_barrier();  // Y
-    stash_b(b_ ^ 1);
-    fetch_b_full(jnn);
-    store_c_full(cur, jc_);
-    fetch_c_full(tgt, jnn);
-    lds_barrier();  // X
-  };
-  auto fast_step1 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jp_v, int jc_v, int b_) __attribute__((always_inline)) {
-    const int jp_ = __builtin_amdgcn_readfirstlane(jp_v), jc_ = __builtin_amdgcn_readfirstlane(jc_v);
-    const int jnn = jc_ + 2 * col_step_s;
-    stash_b(b_ ^ 1);
-    fetch_b_full(jnn);
-    store_c_full(tgt, jp_);
-    fetch_c_full(tgt, jnn);
-    lds_barrier();  // Y
-    multiply(cur, b_);
-    lds_barrier();  // X
-  };
-  // PLAIN: a second instantiation of the kernel; the one without it is the general steps alone (the host takes
-  // it for work items of fewer than kUpdPlainMinBlocks blocks, whose share of general steps is large, and for the
-  // fp32 lower-triangular form: measured)
-  constexpr bool kPlainSteps = PLAIN;
-  const bool wave_plain = kPlainSteps && (wrow0 + 16 <= m) && (b == KMAX) && ext_fit;
-  auto three_plain_steps = [&](int jp_, int jc_) {  // steps at jc_, jc_ + col_step, jc_ + 2 col_step and their prefetches
-    return wave_plain && (jc_ + 4 * col_step + kUpdCols <= col_end) && (wrow0 >= g.skip || jp_ >= g.skip);
-  };
   int jp = col_begin, jc = col_begin;
   bool first = true;
   for (;;) {
-    if (kPlainSteps && !first) {
-      if (grp_s == 0) {
-        while (__builtin_amdgcn_readfirstlane((int)three_plain_steps(jp, jc))) {
-          fast_step0(c0, c2, jc, buf);
-          fast_step0(c1, c0, jc + col_step, buf ^ 1);
-          fast_step0(c2, c1, jc + 2 * col_step, buf);
-          buf ^= 1;
-          jp = jc + 2 * col_step;
-          jc += 3 * col_step;
-        }
-      } else {
-        while (__builtin_amdgcn_readfirstlane((int)three_plain_steps(jp, jc))) {
-          fast_step1(c0, c2, jp, jc, buf);
-          fast_step1(c1, c0, jc, jc + col_step, buf ^ 1);
-          fast_step1(c2, c1, jc + col_step, jc + 2 * col_step, buf);
-          buf ^= 1;
-          jp = jc + 2 * col_step;
-          jc += 3 * col_step;
-        }
-      }
-    }
     block_step(c0, c2, jp, jc, first, buf);
     buf ^= 1;
     first = false;
