@@ -98,40 +98,29 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   const int row0 = panel * kUpdRows;
 
   // ---- left panel -> registers (through LDS for coalesced global reads) -----------------------
+  // 64 k-columns per pass; the loads of the next pass are issued before this pass goes through LDS, so the
+  // passes cost one round trip to memory between them, not one each.
   T afrag[KSTEPS];
   const int wrow0 = row0 + wave * 16;  // first row of this wave
+  constexpr int A_PASSES = KMAX / 64;
+  T va[2][16];  // two staging sets: rows x 64 k-columns, thread -> (row, 2 adjacent columns), 8 rows apart
+  const int a_cp = (tid & 31) * 2, a_r0 = tid >> 5;
+  auto load_a = [&](int pass, T (&v)[16]) __attribute__((always_inline)) {
+    constexpr int RPP = kUpdThreads / 32;
+    static_assert(kUpdRows / RPP == 8, "staging registers");
 #pragma unroll
-  for (int half = 0; half < KMAX / 64; ++half) {  // 64 k-columns per pass
-    {  // rows x 64 k-columns: thread -> (row, 2 adjacent columns); the threads cover RPP rows per pass
-      constexpr int RPP = kUpdThreads / 32, PASSES = kUpdRows / RPP;
-      static_assert(PASSES == 8, "staging registers");
-      const int cp = (tid & 31) * 2, r0 = tid >> 5;
-      T v0[8], v1[8];
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int r = r0 + it * RPP;
-        const int gr = (row0 + r < m) ? row0 + r : m - 1;
-        const int k0 = half * 64 + cp, k1 = k0 + 1;
-        const T* p = g.L + (int64_t)gr * ld;
-        v0[it] = p[k0 < b ? k0 : b - 1];
-        v1[it] = p[k1 < b ? k1 : b - 1];
-        if (!(row0 + r < m && k0 < b)) v0[it] = T(0);
-        if (!(row0 + r < m && k1 < b)) v1[it] = T(0);
-      }
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int r = r0 + it * RPP;
-        smem[r * 65 + cp] = -v0[it];
-        smem[r * 65 + cp + 1] = -v1[it];
-      }
+    for (int it = 0; it < 8; ++it) {
+      const int r = a_r0 + it * RPP;
+      const int gr = (row0 + r < m) ? row0 + r : m - 1;
+      const int k0 = pass * 64 + a_cp, k1 = k0 + 1;
+      const T* p = g.L + (int64_t)gr * ld;
+      v[2 * it] = p[k0 < b ? k0 : b - 1];
+      v[2 * it + 1] = p[k1 < b ? k1 : b - 1];
+      if (!(row0 + r < m && k0 < b)) v[2 * it] = T(0);
+      if (!(row0 + r < m && k1 < b)) v[2 * it + 1] = T(0);
     }
-    lds_barrier();
-#pragma unroll
-    for (int kk = 0; kk < 16; ++kk)
-      afrag[half * 16 + kk] = smem[(wave * 16 + l15) * 65 + kk * 4 + l4];
-    lds_barrier();
-  }
-
+  };
+  load_a(0, va[0]);
   // ---- right-operand block loader: b x 32 block starting at column j0 -> registers -> LDS ------
   // LU:       rows k of U12, cols contiguous columns: thread -> (k = tid / 4, cols / 4 columns)
   // Cholesky: rows j0..j0+cols-1 of L21, b contiguous k: thread -> (row = tid % cols, BPT k-values)
@@ -334,13 +323,37 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // and LDS protocol are those of the general form below, step for step, so the waves of a workgroup may take
   // different forms.  (Barrier Y protects no data, it keeps the wave groups in anti-phase; without it the large
   // updates are 3-10 % slower: measured.)
+  const int cb = __builtin_amdgcn_readfirstlane(col_begin), cs = __builtin_amdgcn_readfirstlane(col_step);
+  const int ce = __builtin_amdgcn_readfirstlane(col_end);
+  const int nblk = (ce - cb + cs - 1) / cs;  // blocks of this item
+  const bool item_plain = PLAIN && __builtin_amdgcn_readfirstlane((int)((wrow0 + 16 <= m) && (b == KMAX) && ext_fit &&
+                                                                        (cb + (nblk - 1) * cs + kUpdCols <= mc) &&
+                                                                        (wrow0 >= g.skip || cb >= g.skip)));
   if constexpr (PLAIN) {
-    const int cb = __builtin_amdgcn_readfirstlane(col_begin), cs = __builtin_amdgcn_readfirstlane(col_step);
-    const int ce = __builtin_amdgcn_readfirstlane(col_end);
-    const int nblk = (ce - cb + cs - 1) / cs;  // blocks of this item
-    const bool item_plain = (wrow0 + 16 <= m) && (b == KMAX) && ext_fit && (cb + (nblk - 1) * cs + kUpdCols <= mc) &&
-                            (wrow0 >= g.skip || cb >= g.skip);
-    if (__builtin_amdgcn_readfirstlane((int)item_plain)) {
+    if (item_plain) {  // the first block's operands are on their way while the left panel goes through LDS
+      fetch_b_full(cb, true);
+      fetch_c_full(c0, cb, true);
+    }
+  }
+#pragma unroll
+  for (int pass = 0; pass < A_PASSES; ++pass) {
+    if (pass + 1 < A_PASSES) load_a(pass + 1, va[(pass + 1) & 1]);
+    {
+      constexpr int RPP = kUpdThreads / 32;
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int r = a_r0 + it * RPP;
+        smem[r * 65 + a_cp] = -va[pass & 1][2 * it];
+        smem[r * 65 + a_cp + 1] = -va[pass & 1][2 * it + 1];
+      }
+    }
+    lds_barrier();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) afrag[pass * 16 + kk] = smem[(wave * 16 + l15) * 65 + kk * 4 + l4];
+    lds_barrier();
+  }
+  if constexpr (PLAIN) {
+    if (item_plain) {
       const int grp_s = __builtin_amdgcn_readfirstlane(wave >> 2);
       auto step0 = [&](acc_t (&cur)[NCB], acc_t (&tgt)[NCB], int jc_, int b_) __attribute__((always_inline)) {
         const int jnn = jc_ + 2 * cs;
@@ -365,8 +378,6 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
         lds_barrier();  // X
       };
       int jc = cb, left = nblk, bf = 0;
-      fetch_b_full(jc, true);
-      fetch_c_full(c0, jc, true);
       stash_b(0);
       fetch_b_full(jc + cs, left > 1);
       fetch_c_full(c1, jc + cs, left > 1);
