@@ -224,7 +224,10 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   // ---- C block of this wave: 16 rows x cols columns = NCB MFMA blocks ------------------------------
   T* const Cw = g.C + (int64_t)wrow0 * ld;
   // (row_of(v, lane) = row_of(v, 0) + row_of(0, lane): the first part is the same for all lanes)
-  const uint32_t coff = (uint32_t)(((int64_t)Mfma<T>::row_of(0, lane) * ld + l15) * (int64_t)sizeof(T));
+  // (a wave whose rows all lie below the matrix takes part in the staging of the right operand only: its C offsets
+  // are out of range from the start)
+  const int wrow0_s = __builtin_amdgcn_readfirstlane(wrow0);
+  const uint32_t coff = wrow0_s >= m ? kOob : (uint32_t)(((int64_t)Mfma<T>::row_of(0, lane) * ld + l15) * (int64_t)sizeof(T));
   auto fetch_c_full = [&](acc_t (&c)[NCB], int j0, bool on) __attribute__((always_inline)) {
     const uint32_t vo = on ? coff : kOob;
 #pragma unroll
@@ -237,15 +240,17 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
       }
   };
   auto store_c_full = [&](const acc_t (&c)[NCB], int j0, bool on) __attribute__((always_inline)) {
-    const uint32_t vo = on ? coff : kOob;
 #pragma unroll
-    for (int q = 0; q < NCB; ++q)
+    for (int q = 0; q < NCB; ++q) {
+      // (the excluded leading block: a condition that is uniform over the wave, per 16 columns)
+      const uint32_t vo = (on && !(wrow0_s < g.skip && j0 + q * 16 < g.skip)) ? coff : kOob;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const uint32_t so = ((uint32_t)Mfma<T>::row_of(v, 0) * (uint32_t)ld + (uint32_t)(j0 + q * 16)) * (uint32_t)sizeof(T);
         if constexpr (sizeof(T) == 8) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2_t, (double)c[q][v]), rs_c, (int)vo, (int)so, 0);
         else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, (float)c[q][v]), rs_c, (int)vo, (int)so, 0);
       }
+    }
   };
   auto fetch_c = [&](acc_t (&c)[NCB], int j0) {
     const bool full = (wrow0 + 16 <= m) && (j0 + kUpdCols <= mc);
@@ -326,9 +331,8 @@ __device__ __forceinline__ void update_segment(const UpdateArgs<T>& g, T* const 
   const int cb = __builtin_amdgcn_readfirstlane(col_begin), cs = __builtin_amdgcn_readfirstlane(col_step);
   const int ce = __builtin_amdgcn_readfirstlane(col_end);
   const int nblk = (ce - cb + cs - 1) / cs;  // blocks of this item
-  const bool item_plain = PLAIN && __builtin_amdgcn_readfirstlane((int)((wrow0 + 16 <= m) && (b == KMAX) && ext_fit &&
-                                                                        (cb + (nblk - 1) * cs + kUpdCols <= mc) &&
-                                                                        (wrow0 >= g.skip || cb >= g.skip)));
+  const bool item_plain = PLAIN && __builtin_amdgcn_readfirstlane((int)((wrow0 + 16 <= m || wrow0 >= m) && (b == KMAX) && ext_fit &&
+                                                                        (cb + (nblk - 1) * cs + kUpdCols <= mc)));
   if constexpr (PLAIN) {
     if (item_plain) {  // the first block's operands are on their way while the left panel goes through LDS
       fetch_b_full(cb, true);
