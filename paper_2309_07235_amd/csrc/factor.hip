@@ -482,7 +482,17 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       const int kk = b + ksh;
       const int64_t lsh = ksh, ush = (KIND == KIND_LU) ? (int64_t)ksh * lda : (int64_t)ksh;
       int r;
-      if (hip_note(hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
+      // solves(k) behind diag(k).  With the chain's counters in use that is a one-wave kernel in front of the solves
+      // that waits in place for the count of factored blocks: on the host a plain launch costs a quarter of a wait
+      // for another stream's event (2.6 against 10 us), and the host's submission time per step is as long as the
+      // step; on the device the solves start a same-stream launch gap after the block is done instead of an event's
+      // round trip.  (Submitted after diag(k), like everything that waits for it.)
+      if (chained && step > 0) {
+        hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, ctx.panel, (const int*)chain, step + 1, chain + 2, wait_ticks);
+        if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
+      } else if (hip_note(hipStreamWaitEvent(ctx.panel, step == 0 ? e_head : e_diag[step & 1], 0), "hipStreamWaitEvent") != 0) {
+        return DLA_ERR_HIP;
+      }
       // the last kernel of the step on this stream carries e_strip
       if ((r = solves(k0, step, ctx.panel, mr > 0 ? e_solve : e_strip)) != DLA_SUCCESS) return r;
       if (mr > 0) {
@@ -597,7 +607,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       if ((r = launch_head<T, KIND>(ha, ctx.head, e_head, &head_wgs)) != DLA_SUCCESS) return r;
       heads_done += head_wgs;
       if (!chained && hip_note(hipStreamWaitEvent(st, e_head, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
-      if ((r = diag(k0 + b, step + 1, st, e_diag[(step + 1) & 1])) != DLA_SUCCESS) return r;
+      if ((r = diag(k0 + b, step + 1, st, chained ? nullptr : e_diag[(step + 1) & 1])) != DLA_SUCCESS) return r;
       return DLA_SUCCESS;
     };
 

@@ -493,6 +493,12 @@ static __global__ void zero_ints_kernel(int* p, int n) {
   if ((int)threadIdx.x < n) p[threadIdx.x] = 0;
 }
 
+// One wave that waits in place until a hand-over counter reaches its target (bounded like every such wait): put in
+// front of a kernel on a stream that would otherwise wait for another stream's event.
+static __global__ void gate_kernel(const int* counter, int target, int* broken, long long wait_ticks) {
+  chain_wait(counter, target, broken, wait_ticks, (int)threadIdx.x);
+}
+
 // A 16 x 16 identity and three zeroed counters (the hand-over self-test's input).
 static __global__ void identity16_kernel(double* a, int* counters) {
   const int t = (int)threadIdx.x;

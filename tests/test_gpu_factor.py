@@ -495,6 +495,7 @@ def test_n8192_fp32_properties(B, oracle):
 
 @pytest.mark.parametrize("m,k", [(1, 1), (17, 16), (200, 48), (333, 128), (1000, 128), (2081, 96),
                                  (300, 256), (1000, 200), (777, 144),   # depth above 128: the two-panel form
+                                 (1952, 256), (2080, 128),              # a last row panel with waves below the matrix
                                  (6200, 256), (6333, 128)])  # large: row-split launches (LU), panel-crossing items (Cholesky)
 @pytest.mark.parametrize("lower", [False, True])
 def test_rank_update_alone(B, oracle, m, k, lower):
