@@ -21,7 +21,7 @@ constexpr int64_t kWideReserveMinRows = 2048;
 constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot gets at least this many
 // Trailing matrices of at least this many rows run their bulk updates two panels at a time (measured:
 // below these sizes the step is bound by the latency chain and the deeper strips only lengthen it).
-constexpr int64_t kDeferMinRowsLu = 3072, kDeferMinRowsChol = 4096;
+constexpr int64_t kDeferMinRowsLu = 2560, kDeferMinRowsChol = 4096;
 // Cholesky updates of at least this many rows use work items that cross row panels (measured: 3-18 %
 // faster from 6000 rows on, slower below 4000; inside the pipeline it pays from about 8000 rows).
 constexpr int64_t kSpanMinRows = 6144;
