@@ -11,13 +11,14 @@ namespace dla {
 
 constexpr int kNumCu = 256;   // compute units of an MI355X
 // Compute units a bulk update leaves to the latency chain and the side path (panel solves, strips) that run beside
-// it: 32, and 64 for the large fp64 LU updates (at least kWideReserveMinRows rows), whose side path -- two panel
-// solves and five strip products per step -- is what the early steps of the call wait for.  Measured with the
+// it: 32, and 64 for the fp64 LU updates of kWideReserveMinRows to kWideReserveMaxRows rows, whose side path -- two
+// panel solves and five strip products per step -- is what those steps of the call wait for.  Measured with the
 // condition-free update kernel (the bulk update got faster, the kernels beside it did not): LU N = 4000 2.07 ->
-// 1.96 ms, N = 6000 4.37 -> 4.20 ms, N = 8192 unchanged; Cholesky does not move with it, fp32 LU loses 4 % at
-// N = 8192 (its bulk update is twice as fast), 80 units and more lose from N = 6000 on.
+// 1.96 ms, N = 6000 4.37 -> 4.17 ms; above about 5000 rows the bulk update is the longer side again (N = 8192:
+// 8.77 ms with 64 units at every size, 8.62 with them below 5120 rows only); Cholesky does not move with it, fp32
+// LU loses 4 % at N = 8192 (its bulk update is twice as fast), 80 units and more lose from N = 6000 on.
 constexpr int kChainCu = 32, kChainCuWide = 64;
-constexpr int64_t kWideReserveMinRows = 2048;
+constexpr int64_t kWideReserveMinRows = 2048, kWideReserveMaxRows = 5120;
 constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot gets at least this many
 // Trailing matrices of at least this many rows run their bulk updates two panels at a time (measured:
 // below these sizes the step is bound by the latency chain and the deeper strips only lengthen it).
@@ -295,12 +296,13 @@ static LookaheadCtx& lookahead_ctx(const void* data) {
 // launches sit on the latency chain and run beside a bulk update that keeps the memory busy).
 // That variant needs a compute unit's registers to itself, so it is used once the bulk update has
 // become small (late steps); beside a large bulk update the 16-deep slabs share compute units better.
-// In fp64 the strips beside a large bulk update are bound by the matrix pipes of the few compute units
-// they get: there 64 x 64 tiles, which do twice the work per LDS byte of 32 x 32 ones, take over earlier
-// (measured with the reserve of 64 units: LU N = 4000 1.99 -> 1.95 ms; fp32 LU N = 8192 loses 3 % with them).
-template <typename T>
+// The strips of the fp64 LU beside a large bulk update are bound by the matrix pipes of the few compute
+// units they get: there 64 x 64 tiles, which do twice the work per LDS byte of 32 x 32 ones, take over earlier
+// (measured with the reserve of 64 units: LU N = 4000 1.99 -> 1.95 ms; fp32 LU and fp64 Cholesky lose 3 % at
+// N = 8192 with them).
+template <typename T, int KIND>
 static GemmSchedule panel_schedule(int64_t mr) {
-  if constexpr (sizeof(T) == 8) return mr <= 1536 ? GemmSchedule{32, 32, 128, 8, 16, 16} : GemmSchedule{64, 64, 16, 4, 32, 32};
+  if constexpr (sizeof(T) == 8 && KIND == KIND_LU) return mr <= 1536 ? GemmSchedule{32, 32, 128, 8, 16, 16} : GemmSchedule{64, 64, 16, 4, 32, 32};
   return mr <= 2304 ? GemmSchedule{32, 32, 128, 8, 16, 16} : GemmSchedule{32, 32, 16, 4, 16, 16};
 }
 
@@ -411,7 +413,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   auto trailing = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, int skip, hipStream_t s,
                       hipEvent_t done) -> int {
     if (auto_tile)
-      return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, skip, mm >= kWideReserveMinRows ? slots_wide : slots,
+      return launch_update<T, KIND>(Lp, KIND == KIND_LU ? Up : Lp, Cp, lda, mm, bb, skip, (mm >= kWideReserveMinRows && mm < kWideReserveMaxRows) ? slots_wide : slots,
                                     s, done);
     const int r = trailing_gemm(Lp, Up, Cp, mm, bb, skip, s);
     if (r != DLA_SUCCESS) return r;
@@ -513,7 +515,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
       if (mr > 0) {
         if (bulk_pending && !after_wide && hip_note(hipStreamWaitEvent(ctx.panel, e_bulk, 0), "hipStreamWaitEvent") != 0) return DLA_ERR_HIP;
         const T* Lr = L21 + bn * lda;  // rows behind block N of the solved column panel
-        const GemmSchedule ps = panel_schedule<T>(mr);
+        const GemmSchedule ps = panel_schedule<T, KIND>(mr);
         GemmGroup<T> g;
         int np = 0, tiles = 0;
         double flops = 0.0;
