@@ -43,7 +43,7 @@ def update_algorithmic_bytes(n, nb=128, lower=False, defer_min_rows=0):
     if nb > 128:
         nb, min_rows = nb // 2, 0
     else:
-        min_rows = defer_min_rows if defer_min_rows > 0 else (4096 if lower else 2560)
+        min_rows = defer_min_rows if defer_min_rows > 0 else 2560  # the library's fp64 defaults (fp32 Cholesky: 4096)
 
     def region(rows, lead):
         if lower:

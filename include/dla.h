@@ -103,7 +103,7 @@ typedef struct {
                     debuggers); -1 = default (1)                                                */
   dla_gemm_params update;
   int defer_min_rows; /* nb = 128 only: bulk updates run two panels deep while the trailing matrix has
-                         at least this many rows.  0 = library default (2560 for LU, 4096 for Cholesky),
+                         at least this many rows.  0 = library default (2560; 4096 for fp32 Cholesky),
                          -1 = never, 1 = whenever possible.  Ignored for other block sizes.      */
 } dla_factor_params;
 

@@ -11,18 +11,19 @@ namespace dla {
 
 constexpr int kNumCu = 256;   // compute units of an MI355X
 // Compute units a bulk update leaves to the latency chain and the side path (panel solves, strips) that run beside
-// it: 32, and 64 for the fp64 LU updates of kWideReserveMinRows to kWideReserveMaxRows rows, whose side path -- two
-// panel solves and five strip products per step -- is what those steps of the call wait for.  Measured with the
-// condition-free update kernel (the bulk update got faster, the kernels beside it did not): LU N = 4000 2.07 ->
-// 1.96 ms, N = 6000 4.37 -> 4.17 ms; above about 5000 rows the bulk update is the longer side again (N = 8192:
-// 8.77 ms with 64 units at every size, 8.62 with them below 5120 rows only); Cholesky does not move with it, fp32
-// LU loses 4 % at N = 8192 (its bulk update is twice as fast), 80 units and more lose from N = 6000 on.
+// it: 32, and 64 for the fp64 updates of kWideReserveMinRows to kWideReserveMaxRows rows, whose side path is what
+// those steps of the call wait for.  Measured with the condition-free update kernel (the bulk update got faster,
+// the kernels beside it did not): LU N = 4000 2.07 -> 1.96 ms, N = 6000 4.37 -> 4.17 ms; above about 5000 rows the
+// bulk update is the longer side again (LU N = 8192: 8.77 ms with 64 units at every size, 8.62 with them below 5120
+// rows only).  Cholesky gains with it once it also defers its bulk updates down to 2560 rows (N = 4000 1.64 -> 1.59,
+// N = 6000 3.14 -> 2.97, N = 8192 5.59 -> 5.44 ms; neither change helps alone).  fp32, whose bulk update is twice
+// as fast, loses with 64 (LU N = 8192 4 %); 80 units and more lose from N = 6000 on.
 constexpr int kChainCu = 32, kChainCuWide = 64;
 constexpr int64_t kWideReserveMinRows = 2048, kWideReserveMaxRows = 5120;
 constexpr int kWideMinBlocks = 2;  // 64-column update blocks once every slot gets at least this many
 // Trailing matrices of at least this many rows run their bulk updates two panels at a time (measured:
 // below these sizes the step is bound by the latency chain and the deeper strips only lengthen it).
-constexpr int64_t kDeferMinRowsLu = 2560, kDeferMinRowsChol = 4096;
+constexpr int64_t kDeferMinRowsLu = 2560, kDeferMinRowsChol = 2560, kDeferMinRowsCholF32 = 4096;
 // Cholesky updates of at least this many rows use work items that cross row panels (measured: 3-18 %
 // faster from 6000 rows on, slower below 4000; inside the pipeline it pays from about 8000 rows).
 constexpr int64_t kSpanMinRows = 6144;
@@ -63,7 +64,7 @@ int resolve_factor_params(dla_dtype dt, int64_t n, const dla_factor_params* in, 
   plan->nb = two_level ? b / 2 : b;
   plan->lookahead = la;
   plan->two_level = two_level || (b == kNbMax && defer != -1 && !tiled);
-  plan->defer_min_rows = two_level ? 0 : (defer > 0 ? defer : (op == OP_SUB ? kDeferMinRowsLu : kDeferMinRowsChol));
+  plan->defer_min_rows = two_level ? 0 : (defer > 0 ? defer : (op == OP_SUB ? kDeferMinRowsLu : (dt == DLA_F64 ? kDeferMinRowsChol : kDeferMinRowsCholF32)));
   return resolve_schedule(dt, in ? &in->update : nullptr, op, upd);
 }
 
@@ -388,7 +389,7 @@ static int factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* p,
   // update write above it, and the triangle is zeroed at the end instead.
   const bool early_zero = KIND == KIND_CHOL && pipelined && nb == kUpdRows && auto_tile;
   const int slots = pipelined ? kNumCu - kChainCu : kNumCu;
-  const int slots_wide = pipelined ? kNumCu - ((KIND == KIND_LU && sizeof(T) == 8) ? kChainCuWide : kChainCu) : kNumCu;
+  const int slots_wide = pipelined ? kNumCu - (sizeof(T) == 8 ? kChainCuWide : kChainCu) : kNumCu;
   auto trailing_gemm = [&](const T* Lp, const T* Up, T* Cp, int64_t mm, int bb, int skip, hipStream_t s) -> int {
     const GemmSchedule us = update_schedule(mm);
     if (skip == 0) {
