@@ -28,6 +28,13 @@
 // wave and iteration, right-operand bytes per iteration and the pipeline are the same as at depth 128
 // with NCB = 2.
 //
+// Two forms of a work item (PLAIN): the general one, whose steps test whether a block exists, is ragged or
+// belongs to the excluded leading block, and -- for a wave whose rows and an item whose blocks all lie inside
+// the matrix at full depth -- one without a condition in its steps: buffer loads and stores (scalar base and
+// offset, one constant per-lane offset), ends of the item and excluded blocks switched off through an
+// out-of-range offset.  Only in straight-line code does the compiler count the loads in flight exactly; behind
+// the general form's branches it waits for all of them before every use.
+//
 // Work list: (row panel, column range) items of roughly equal size, derived from blockIdx alone
 // (update_kernel).  One launch cuts every row panel into whole work items, which leaves compute units
 // idle when the panel count does not divide them well: an LU update is then given to two launches by
