@@ -525,6 +525,30 @@ def test_rank_update_alone(B, oracle, m, k, lower):
     assert max_rel_err(got[k:, k:], exp[k:, k:]) <= TOL64
 
 
+@pytest.mark.parametrize("m,k", [(1952, 256), (2080, 128), (333, 128), (300, 256)])
+@pytest.mark.parametrize("lower", [False, True])
+def test_rank_update_leaves_the_rows_below_the_matrix_alone(B, oracle, m, k, lower):
+    """The last row panel of an update is partial: its waves below the matrix (and the lanes of a wave that straddles
+    the last row) must neither store nor count on what lies there.  The matrix is followed in memory by guard rows
+    of NaN; they must still be NaN bit for bit afterwards, and the result must not have picked any up."""
+    import torch
+    announce(f"rank_update with guard rows m={m} k={k} lower={lower}")
+    n = m + k
+    guard = 160  # more than the 128 rows of a row panel
+    A = inputs.uniform_matrix(11, 5, n, n)
+    a = torch.full((n + guard, n), float("nan"), dtype=torch.float64, device="cuda")
+    a[:n].copy_(torch.from_numpy(A))
+    L, R, C = a[k:n, :k], a[:k, k:], a[k:n, k:]
+    B.dla_rank_update(lower, L, R, C)
+    torch.cuda.synchronize()
+    got = a.cpu().numpy()
+    assert np.isnan(got[n:]).all(), "rows below the matrix were written"
+    assert not np.isnan(got[:n]).any(), "the update read rows below the matrix into its result"
+    if not lower:
+        exp = A[k:, k:] - oracle_product(oracle, A[k:, :k], A[:k, k:])
+        assert max_rel_err(got[k:n, k:], exp) <= TOL64
+
+
 def test_back_to_back_calls_share_the_helper_streams(B, oracle):
     """Five factorisations of different sizes and kinds enqueued on one side stream without any
     synchronisation in between (the look-ahead helper streams and events are shared by all calls):
