@@ -154,9 +154,10 @@ int cholesky_factor(void* d_a, int64_t n, int64_t lda, dla_dtype dt, const dla_f
  *   d_b          device, n x nrhs, row-major with leading dimension ldb (every column is one
  *                right-hand side); overwritten by X.  Must not overlap the factor.
  *   d_workspace / workspace_bytes   device scratch of at least solve_workspace_bytes(n, nrhs, dt)
- *                bytes, 256-byte aligned: the inverted 256 x 256 diagonal blocks of the factor
- *                for the two substitutions (5 KB per row of the factor in fp64) and the
- *                intermediate n x nrhs solution of the forward pass.
+ *                bytes, 256-byte aligned: per 256 rows of the factor and substitution a 256 x 256
+ *                inverted diagonal block and its 256 x 512 product with the factor's blocks beside
+ *                it (13 KB per row of the factor in fp64), and two n x nrhs areas for the
+ *                solutions of the forward and the backward pass.
  * n == 0 or nrhs == 0 is a successful no-op that needs no workspace.  A zero on the factor's diagonal
  * gives infinities or NaNs in X; nothing is reported (the factorisation's d_info already said so).
  */

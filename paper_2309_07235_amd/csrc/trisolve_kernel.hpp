@@ -1,12 +1,12 @@
 // Solving with the factors (paper, Section "Introduction": LU and Cholesky are named as the
 // factorisations behind solving systems of linear equations):  A X = B  becomes  L Y = B, U X = Y
 // after lu_factor and  L Y = B, L^T X = Y  after cholesky_factor.  The host driver walks the
-// triangular matrix in blocks of up to 128 rows.  The blocks' own triangular systems are taken off
-// the chain of the substitution by inverting every diagonal block up front (this kernel: one
-// workgroup per block, all blocks at once, independent of the right-hand sides), so that each step of
-// the chain is two small products on the tiled GEMM: X_k = W_k * B_k, then the rows still open
-// -= (factor's block column k) * X_k.  The host pairs the 128-row inverses into inverses of 256-row
-// blocks (two more small products per pair, all pairs at once), which halves the steps of the chain.
+// triangular matrix in blocks of rows.  The blocks' own triangular systems are taken off the chain
+// of the substitution by inverting every diagonal block up front (this kernel: one workgroup per
+// 128-row block, all blocks at once, independent of the right-hand sides), so that a step of the
+// chain is small products on the tiled GEMM.  The host pairs the 128-row inverses into inverses of
+// 256-row blocks (two more small products per pair, all pairs at once), which halves the steps of
+// the chain, and asks for the negated inverses (unit = -1) because its chain subtracts.
 //
 // The inversion is the panel solve of the factorisations run on the identity: the block is brought
 // to the form head_solve takes, lower triangular M' with 16 x 16 sub-blocks whose diagonal ones are
@@ -15,7 +15,8 @@
 //   TRI_LOWER_UNIT   M' = L (unit diagonal implied; LU forward pass)
 //   TRI_LOWER        M' = L (Cholesky forward pass)
 //   TRI_UPPER        M' = J U J    with J the reversal of the block's rows (LU backward pass)
-//   TRI_LOWER_TRANS  M' = J L^T J  (Cholesky backward pass; L^T is never formed in memory)
+//   TRI_LOWER_TRANS  M' = J L^T J  (the inverse of L^T; the host driver reads the inverse of L transposed
+//                    instead and does not use this mode)
 // The result is stored un-reversed, W = J M'^-1 J.  A block shorter than a multiple of 16 is padded
 // with the identity.
 #pragma once
@@ -65,10 +66,12 @@ struct TriPrepareArgs {
   int64_t lda;
   int64_t n;
   T* out;       // one kTriPair x kTriPair area per pair of diagonal blocks
+  T unit;       // 1: the inverses themselves; -1: the negated inverses (the substitution runs on -I)
 };
 
+// The work of one workgroup: diagonal block `block` of g's factor.
 template <typename T, int MODE>
-__global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepareArgs<T> g) {
+__device__ __forceinline__ void tri_prepare_block(const TriPrepareArgs<T>& g, const int block) {
   constexpr int NB = kNbMax / kIb;
   constexpr int NTRI = NB * (NB + 1) / 2;
   constexpr bool REV = MODE == TRI_UPPER || MODE == TRI_LOWER_TRANS;
@@ -78,7 +81,7 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
 
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, l4 = lane >> 4;
-  const int64_t k0 = (int64_t)blockIdx.x * kNbMax;
+  const int64_t k0 = (int64_t)block * kNbMax;
   const int b = (int)(g.n - k0 < kNbMax ? g.n - k0 : kNbMax);
   const int nblk = (b + kIb - 1) / kIb, bp = nblk * kIb;
   const int64_t lda = g.lda;
@@ -145,7 +148,7 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
   // out holds W = M^-1 for the block in its own (un-reversed) index space, row-major, so that the
   // solve itself is the plain product W * B; what lies outside the b x b block is never read.
   using acc_t = typename Mfma<T>::acc_t;
-  T* const out = g.out + (int64_t)(blockIdx.x >> 1) * (kTriPair * kTriPair) + (blockIdx.x & 1) * (kNbMax * kTriPair + kNbMax);
+  T* const out = g.out + (int64_t)(block >> 1) * (kTriPair * kTriPair) + (block & 1) * (kNbMax * kTriPair + kNbMax);
   for (int pass = 0; pass < NB / (kTriThreads / 64); ++pass) {
     const int slice = pass * (kTriThreads / 64) + wave;
     if (slice < nblk) {  // uniform per wave
@@ -153,7 +156,7 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
 #pragma unroll
       for (int s = 0; s < NB; ++s)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[s][v] = (s * kIb + 4 * l4 + v == slice * kIb + l15) ? T(1) : T(0);
+        for (int v = 0; v < 4; ++v) acc[s][v] = (s * kIb + 4 * l4 + v == slice * kIb + l15) ? g.unit : T(0);
       if (nblk == NB) head_solve<T, true>(tri, kIb + 1, 1, nblk, lane, acc);
       else head_solve<T, false>(tri, kIb + 1, 1, nblk, lane, acc);
       const int cc = orig(slice * kIb + l15);
@@ -169,6 +172,20 @@ __global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepa
       }
     }
   }
+}
+
+template <typename T, int MODE>
+__global__ void __launch_bounds__(kTriThreads) tri_prepare_kernel(const TriPrepareArgs<T> g) {
+  tri_prepare_block<T, MODE>(g, (int)blockIdx.x);
+}
+
+// Two sets of inverses of the same factor in one launch (they are independent): the first half of the
+// grid works on ga in MODE_A, the second half on gb in MODE_B.
+template <typename T, int MODE_A, int MODE_B>
+__global__ void __launch_bounds__(kTriThreads) tri_prepare_both_kernel(const TriPrepareArgs<T> ga, const TriPrepareArgs<T> gb) {
+  const int half = (int)(gridDim.x >> 1);
+  if ((int)blockIdx.x < half) tri_prepare_block<T, MODE_A>(ga, (int)blockIdx.x);
+  else tri_prepare_block<T, MODE_B>(gb, (int)blockIdx.x - half);
 }
 
 }  // namespace dla

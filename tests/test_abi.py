@@ -169,8 +169,9 @@ def test_argument_errors_are_reported_without_gpu_work(B):
         assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, vp(0x1008), 1 << 20, None) == B.DLA_ERR_WORKSPACE
         assert solve(None, 0, 1, None, 2, 2, B.DLA_F64, None, 0, None) == 0  # nothing to solve
         assert solve(fake, 8, 8, None, 0, 1, B.DLA_F64, None, 0, None) == 0  # no right-hand side
-    assert L.solve_workspace_bytes(4000, 63, B.DLA_F64) == (2 * 16 * (256 * 256 + 128 * 128) + 4000 * 64) * 8
-    assert L.solve_workspace_bytes(1, 1, B.DLA_F32) == (2 * (256 * 256 + 128 * 128) + 2) * 4
+    # per 256-row block and pass: a 256 x 256 inverse, a 128 x 128 intermediate, a 256 x 512 look-back product; two n x nrhs areas
+    assert L.solve_workspace_bytes(4000, 63, B.DLA_F64) == (2 * 16 * (256 * 256 + 128 * 128 + 256 * 512) + 2 * 4000 * 64) * 8
+    assert L.solve_workspace_bytes(1, 1, B.DLA_F32) == (2 * (256 * 256 + 128 * 128 + 256 * 512) + 2 * 2) * 4
     assert L.solve_workspace_bytes(-1, 1, B.DLA_F64) == 0 and L.solve_workspace_bytes(8, -1, B.DLA_F64) == 0
     assert L.solve_workspace_bytes(8, 1, 9) == 0
     assert L.dla_gemm(4, fake, 4, fake, 8, fake, 8, 8, 8, 8, B.DLA_F64, None, None) == -3  # A is k x m: lda >= m
