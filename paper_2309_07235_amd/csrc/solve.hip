@@ -23,6 +23,7 @@
 // inverses of its own.  The forward pass leaves Y in the workspace and spoils B; the backward pass
 // builds X in a second workspace area and stores each finished block to B as well.
 #include "trisolve_kernel.hpp"
+#include "skinny_kernel.hpp"
 #include "host_common.hpp"
 
 namespace dla {
@@ -46,6 +47,20 @@ static int launch_prepare_both(const TriPrepareArgs<T>& a, const TriPrepareArgs<
   const int grid = 2 * (int)((a.n + kNbMax - 1) / kNbMax);
   ProfileScope scope(PHASE_TRSM, 0.0, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kTriThreads), trisolve_lds_bytes<T>(), st, a, b);
+  return launch_status(__func__);
+}
+
+template <typename T>
+static int launch_skinny(bool at, const SkinnyGroup<T>& g, int workgroups, int kmax, double flops, hipStream_t st) {
+  ProfileScope scope(PHASE_GEMM, flops, st);
+  const dim3 grid((unsigned)workgroups), block(kSkinnyThreads);
+  if (kmax <= 256) {
+    if (at) hipLaunchKernelGGL((skinny_kernel<T, true, 16>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((skinny_kernel<T, false, 16>), grid, block, 0, st, g);
+  } else {
+    if (at) hipLaunchKernelGGL((skinny_kernel<T, true, 32>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((skinny_kernel<T, false, 32>), grid, block, 0, st, g);
+  }
   return launch_status(__func__);
 }
 
@@ -123,12 +138,9 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
   auto rows_of = [&](int i) { return n - (int64_t)i * sb < sb ? n - (int64_t)i * sb : sb; };
   auto Nf = [&](int i) { return wf + (int64_t)i * sb * sb; };
   auto Nb = [&](int i) { return wb + (int64_t)i * sb * sb; };
-  // The products are skinny (k <= 512, few columns): small tiles spread them over the compute units.  Up to
-  // 128 right-hand sides a launch of the chain is a handful of tiles per compute unit and what it costs is the
-  // number of k slabs a tile walks through (a round trip to memory each): 128-deep slabs (N = 4000, 64
-  // right-hand sides: 0.49 ms against 0.61 ms with 16-deep ones; with 256 right-hand sides 0.80 against 0.69).
+  // Above 128 right-hand sides the chain's launches run on the tiled GEMM: 32 x 32 tiles up to 256, 64 x 64 above.
   const GemmSchedule small = GemmSchedule{32, 32, 16, 4, 16, 16};
-  const GemmSchedule sch = nrhs <= 128 ? GemmSchedule{32, 32, 128, 8, 16, 16} : nrhs <= 256 ? small : GemmSchedule{64, 64, 16, 2, 32, 32};
+  const GemmSchedule sch = nrhs <= 256 ? small : GemmSchedule{64, 64, 16, 2, 32, 32};
   const GemmSchedule wide = GemmSchedule{64, 64, 16, 4, 32, 32};  // the 256 x 512 products of the pre-pass
   int rc;
   // ---- pre-pass: every target of a subtracting product that stands for a plain one starts at zero
@@ -201,7 +213,34 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     T *c, *c2;
     int64_t la, lb, lc, lc2, M, K;
   };
+  // Up to 128 right-hand sides a launch of the chain is a few hundred 16 x 16 blocks and what matters is how soon
+  // its longest product ends: the skinny kernel (one block per workgroup, k split over its waves; N = 4000, 64
+  // right-hand sides 0.39 ms against 0.48 ms on 32 x 32 tiles with 128-deep slabs, 0.61 ms with 16-deep ones);
+  // above that the tiled GEMM.
+  const bool skinny = nrhs <= 128;
+  static_assert(2 * kTriPair <= kSkinnyMaxK, "the look-back product's depth");
   auto launch_parts = [&](int op, const Part* parts, int count) -> int {
+    if (skinny) {
+      SkinnyGroup<T> sg;
+      int np = 0, wgs = 0, kmax = 0;
+      double flops = 0.0;
+      for (int q = 0; q < count; ++q) {
+        const Part& P = parts[q];
+        if (P.M <= 0 || P.K <= 0) continue;
+        SkinnyPart<T>& sp = sg.part[np++];
+        // part (c), the rows still open, is the one with many blocks and the factor as its left operand
+        const int wide = (q == 2 && nrhs > 16 && P.K <= 256) ? 1 : 0;
+        sp = SkinnyPart<T>{P.a, P.b, P.c, P.c2, P.la, P.lb, P.lc, P.lc2, (int)P.M, (int)nrhs, (int)P.K,
+                           (int)((nrhs + (wide ? 31 : 15)) / (wide ? 32 : 16)), wgs, wide};
+        wgs += (int)((P.M + 15) / 16) * sp.tiles_n;
+        kmax = P.K > kmax ? (int)P.K : kmax;
+        flops += 2.0 * (double)P.M * (double)nrhs * (double)P.K;
+      }
+      if (np == 0) return DLA_SUCCESS;
+      for (int q = np; q < kSkinnyMaxParts; ++q) sg.part[q] = sg.part[0];
+      sg.nparts = np;
+      return launch_skinny<T>(op == OP_SUB_TN, sg, wgs, kmax, flops, st);
+    }
     GemmGroup<T> g;
     int np = 0, tiles = 0;
     double flops = 0.0;

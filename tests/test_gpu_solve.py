@@ -38,11 +38,12 @@ def _gpu_solve(B, kind, F, rhs, dtype=None):
     return to_host(b)
 
 
-# sizes span one sub-block, one block, the first ragged block, several blocks with a ragged tail;
-# right-hand sides span one, a ragged slice of 16, one workgroup (64) and several
+# sizes span one sub-block, one block, the first ragged block, several blocks with a ragged tail, a last block of
+# one row behind four whole ones (odd leading dimension); right-hand sides span one, a ragged slice of 16, one and
+# two column blocks per workgroup of the chain's kernel up to its limit (128), and the tiled GEMM's ranges above
 @pytest.mark.parametrize("kind", ["lu", "chol"])
 @pytest.mark.parametrize("n,nrhs", [(1, 1), (7, 3), (16, 1), (100, 5), (128, 64), (129, 1), (300, 17), (1000, 130),
-                                    (517, 260)])
+                                    (517, 260), (1025, 33), (900, 128), (770, 50), (1300, 16)])
 def test_solve_matches_oracle(B, oracle, kind, n, nrhs):
     announce(f"solve {kind} n={n} nrhs={nrhs} f64")
     A, F = _factor(oracle, kind, n, 21)
@@ -54,7 +55,7 @@ def test_solve_matches_oracle(B, oracle, kind, n, nrhs):
 
 
 @pytest.mark.parametrize("kind", ["lu", "chol"])
-@pytest.mark.parametrize("n,nrhs", [(129, 3), (700, 40)])
+@pytest.mark.parametrize("n,nrhs", [(129, 3), (700, 40), (1025, 20)])
 def test_solve_fp32(B, oracle, kind, n, nrhs):
     import torch
     announce(f"solve {kind} n={n} nrhs={nrhs} f32")
