@@ -38,9 +38,15 @@ struct SkinnyPart {
   int64_t lda, ldb, ldc, ldc2;
   int M, N, K;
   int tiles_n;     // workgroups per block row: 16-column blocks, or pairs of them (wide)
-  int tile_begin;  // first workgroup of this product
+  int tile_begin;  // first workgroup of this product (skinny_workgroups() of them)
   int wide;        // 1: a workgroup owns two adjacent 16-column blocks (K <= 256 only)
 };
+
+// Workgroups of a product with M rows and tiles_n workgroups per block row (block rows padded to groups of kNumXcd).
+inline int skinny_workgroups(int64_t M, int tiles_n) {
+  const int tiles_m = (int)((M + 15) / 16);
+  return (tiles_m + kNumXcd - 1) / kNumXcd * kNumXcd * tiles_n;
+}
 
 template <typename T>
 struct SkinnyGroup {
@@ -54,7 +60,12 @@ struct SkinnyGroup {
 template <typename T, bool AT, int SMAX, int NB>
 __device__ __forceinline__ void skinny_block(const SkinnyPart<T>& P, const int local, T* __restrict__ red) {
   using acc_t = typename Mfma<T>::acc_t;
-  const int m0 = (local / P.tiles_n) * 16, n0 = (local % P.tiles_n) * (16 * NB);
+  // Workgroups are dealt to the XCDs round-robin; the column tiles of one block row are kXcdStride workgroups
+  // apart so that they meet in one XCD's L2 (they read the same rows of the left operand).  A product's
+  // workgroup count is padded to whole groups of kNumXcd block rows; the padding has nothing to do.
+  const int ti = (local / (kNumXcd * P.tiles_n)) * kNumXcd + local % kNumXcd, tj = (local / kNumXcd) % P.tiles_n;
+  if (ti * 16 >= P.M) return;  // uniform
+  const int m0 = ti * 16, n0 = tj * (16 * NB);
   const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l15 = lane & 15, l4 = lane >> 4;
   const int M = P.M, N = P.N, K = P.K;

@@ -232,7 +232,7 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
         const int wide = (q == 2 && nrhs > 16 && P.K <= 256) ? 1 : 0;
         sp = SkinnyPart<T>{P.a, P.b, P.c, P.c2, P.la, P.lb, P.lc, P.lc2, (int)P.M, (int)nrhs, (int)P.K,
                            (int)((nrhs + (wide ? 31 : 15)) / (wide ? 32 : 16)), wgs, wide};
-        wgs += (int)((P.M + 15) / 16) * sp.tiles_n;
+        wgs += skinny_workgroups(P.M, sp.tiles_n);
         kmax = P.K > kmax ? (int)P.K : kmax;
         flops += 2.0 * (double)P.M * (double)nrhs * (double)P.K;
       }
