@@ -212,6 +212,7 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     const T *a, *b;
     T *c, *c2;
     int64_t la, lb, lc, lc2, M, K;
+    int many;  // 1 for product (c): many blocks, the factor as its left operand
   };
   // Up to 128 right-hand sides a launch of the chain is a few hundred 16 x 16 blocks and what matters is how soon
   // its longest product ends: the skinny kernel (one block per workgroup, k split over its waves; N = 4000, 64
@@ -228,8 +229,7 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
         const Part& P = parts[q];
         if (P.M <= 0 || P.K <= 0) continue;
         SkinnyPart<T>& sp = sg.part[np++];
-        // part (c), the rows still open, is the one with many blocks and the factor as its left operand
-        const int wide = (q == 2 && nrhs > 16 && P.K <= 256) ? 1 : 0;
+        const int wide = (P.many && nrhs > 16 && P.K <= 256) ? 1 : 0;
         sp = SkinnyPart<T>{P.a, P.b, P.c, P.c2, P.la, P.lb, P.lc, P.lc2, (int)P.M, (int)nrhs, (int)P.K,
                            (int)((nrhs + (wide ? 31 : 15)) / (wide ? 32 : 16)), wgs, wide};
         wgs += skinny_workgroups(P.M, sp.tiles_n);
@@ -271,13 +271,15 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     const int64_t k0 = (int64_t)k * sb;
     const int64_t c0 = (int64_t)(k >= 1 ? k - 1 : 0) * sb, kc = k0 + sb - c0;  // rows of Y that M_{k+1} multiplies
     const int64_t r3 = k0 + 3 * sb;                                            // first row of part (c)
+    // (c) first: its workgroups wait longest for their operand (the factor, from HBM), so they are dispatched
+    // first (N = 4000, 64 right-hand sides: 0.365 ms against 0.380 ms with (c) last)
     Part parts[3] = {
-        {mf + (int64_t)(k + 1) * sb * 2 * sb, Y + c0 * ldy, Y + (k0 + sb) * ldy, nullptr, 2 * sb, ldy, ldy, 0, rows_of(k + 1), kc},
         {},
+        {mf + (int64_t)(k + 1) * sb * 2 * sb, Y + c0 * ldy, Y + (k0 + sb) * ldy, nullptr, 2 * sb, ldy, ldy, 0, rows_of(k + 1), kc, 0},
         {}};
+    if (r3 < n) parts[0] = Part{F + r3 * lda + k0, Y + k0 * ldy, B + r3 * ldb, nullptr, lda, ldy, ldb, 0, n - r3, sb, 1};
     if (k + 2 < nblk)
-      parts[1] = Part{Nf(k + 2), B + (k0 + 2 * sb) * ldb, Y + (k0 + 2 * sb) * ldy, nullptr, sb, ldb, ldy, 0, rows_of(k + 2), rows_of(k + 2)};
-    if (r3 < n) parts[2] = Part{F + r3 * lda + k0, Y + k0 * ldy, B + r3 * ldb, nullptr, lda, ldy, ldb, 0, n - r3, sb};
+      parts[2] = Part{Nf(k + 2), B + (k0 + 2 * sb) * ldb, Y + (k0 + 2 * sb) * ldy, nullptr, sb, ldb, ldy, 0, rows_of(k + 2), rows_of(k + 2), 0};
     if ((rc = launch_parts(OP_SUB, parts, 3)) != DLA_SUCCESS) return rc;
   }
   // ---- backward.  Z_k and then X_k live in rows k of X (finished blocks are stored to B as well); Y is
@@ -297,12 +299,12 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     const int64_t r1 = k0 - 2 * sb;                               // part (c) covers rows 0 .. r1
     const T* const m_prev = mb + (int64_t)(k - 1) * sb * 2 * sb;
     Part parts[3] = {
-        {m_prev, X + k0 * ldy, X + (k0 - sb) * ldy, B + (k0 - sb) * ldb, KIND == KIND_LU ? 2 * sb : sb, ldy, ldy, ldb, sb, kc},
         {},
+        {m_prev, X + k0 * ldy, X + (k0 - sb) * ldy, B + (k0 - sb) * ldb, KIND == KIND_LU ? 2 * sb : sb, ldy, ldy, ldb, sb, kc, 0},
         {}};
+    if (r1 > 0) parts[0] = Part{KIND == KIND_LU ? F + k0 : F + k0 * lda, X + k0 * ldy, Y, nullptr, lda, ldy, ldy, 0, r1, rows_of(k), 1};
     if (k >= 2)
-      parts[1] = Part{KIND == KIND_LU ? Nb(k - 2) : Nf(k - 2), Y + (k0 - 2 * sb) * ldy, X + (k0 - 2 * sb) * ldy, nullptr, sb, ldy, ldy, 0, sb, sb};
-    if (r1 > 0) parts[2] = Part{KIND == KIND_LU ? F + k0 : F + k0 * lda, X + k0 * ldy, Y, nullptr, lda, ldy, ldy, 0, r1, rows_of(k)};
+      parts[2] = Part{KIND == KIND_LU ? Nb(k - 2) : Nf(k - 2), Y + (k0 - 2 * sb) * ldy, X + (k0 - 2 * sb) * ldy, nullptr, sb, ldy, ldy, 0, sb, sb, 0};
     if ((rc = launch_parts(BOP, parts, 3)) != DLA_SUCCESS) return rc;
   }
   return DLA_SUCCESS;
