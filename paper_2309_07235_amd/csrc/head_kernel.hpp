@@ -291,12 +291,22 @@ __global__ void __launch_bounds__(kSolveThreads) solve_kernel(const SolveArgs<T>
   const int t = slice0 + (l15 < t_valid ? l15 : t_valid - 1);
   T* const prhs = x_job ? g.top + (int64_t)(4 * l4) * lda + t : g.side + (int64_t)t * lda + 4 * l4;
   const int64_t ks = x_job ? lda : 1;
+  // A lane of the column panel's job owns runs of four consecutive elements of its row: read and written as
+  // pairs where the panel's alignment allows (16 rows per instruction cost the texture path 16 look-ups
+  // whatever the width, so half the instructions is half the look-ups).
+  using vec2_t = typename Mfma<T>::vec2_t;
+  const bool pairs = !x_job && lda % 2 == 0 && (uintptr_t)g.side % (2 * sizeof(T)) == 0;  // uniform
   acc_t acc[NB];
 #pragma unroll
   for (int s = 0; s < NB; ++s) {
     if (job_on && s < nblk) {
+      if (pairs) {
+        const vec2_t lo = *reinterpret_cast<const vec2_t*>(prhs + s * kIb), hi = *reinterpret_cast<const vec2_t*>(prhs + s * kIb + 2);
+        acc[s] = acc_t{lo[0], lo[1], hi[0], hi[1]};
+      } else {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc[s][v] = prhs[(int64_t)(s * kIb + v) * ks];
+        for (int v = 0; v < 4; ++v) acc[s][v] = prhs[(int64_t)(s * kIb + v) * ks];
+      }
     } else {
       acc[s] = acc_t{0, 0, 0, 0};
     }
@@ -342,8 +352,13 @@ __global__ void __launch_bounds__(kSolveThreads) solve_kernel(const SolveArgs<T>
 #pragma unroll
     for (int s = 0; s < NB; ++s) {
       if (s < nblk) {
+        if (pairs) {
+          *reinterpret_cast<vec2_t*>(prhs + s * kIb) = vec2_t{acc[s][0], acc[s][1]};
+          *reinterpret_cast<vec2_t*>(prhs + s * kIb + 2) = vec2_t{acc[s][2], acc[s][3]};
+        } else {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) prhs[(int64_t)(s * kIb + v) * ks] = acc[s][v];
+          for (int v = 0; v < 4; ++v) prhs[(int64_t)(s * kIb + v) * ks] = acc[s][v];
+        }
       }
     }
   }
