@@ -71,6 +71,12 @@ def _load() -> ctypes.CDLL:
     lib.lu_solve.restype = ci
     lib.cholesky_solve.argtypes = lib.lu_solve.argtypes
     lib.cholesky_solve.restype = ci
+    for fn in (lib.lu_solve_prepared, lib.cholesky_solve_prepared):
+        fn.argtypes = lib.lu_solve.argtypes
+        fn.restype = ci
+    for fn in (lib.lu_solve_prepare, lib.cholesky_solve_prepare):
+        fn.argtypes = [vp, i64, i64, ci, vp, sz, vp]
+        fn.restype = ci
     lib.factor_workspace_bytes.argtypes = [i64, ci, ctypes.POINTER(FactorParams)]
     lib.factor_workspace_bytes.restype = sz
     lib.mm3.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i64, i64, i64, ci,
@@ -247,6 +253,42 @@ def lu_solve(lu, b, workspace=None, stream=None):
 def cholesky_solve(l, b, workspace=None, stream=None):
     """Overwrites b with X, (L*L^T)*X = b, from cholesky_factor's output (see dla.h: cholesky_solve)."""
     return _solve(lib.cholesky_solve, "cholesky_solve", l, b, workspace, stream)
+
+
+def _solve_prepare(fn, name: str, f, max_nrhs: int, workspace, stream):
+    n = f.shape[0]
+    if f.ndim != 2 or f.shape[1] != n:
+        raise ValueError(f"{name}: the factor must be square")
+    dt = _dtype_code(f)
+    fp, ldf = _matrix(f, "factor")
+    ws, wsp, wsb = _workspace(solve_workspace_bytes(n, max_nrhs, dt), f.device, workspace)
+    _check(fn(fp, n, ldf, dt, wsp, wsb, ctypes.c_void_p(_stream_ptr(stream))), name)
+    return ws
+
+
+def lu_solve_prepare(lu, max_nrhs: int, workspace=None, stream=None):
+    """The part of lu_solve that does not depend on the right-hand sides (see dla.h: lu_solve_prepare).  Returns the
+    workspace, sized for up to max_nrhs right-hand sides, to pass to lu_solve_prepared."""
+    return _solve_prepare(lib.lu_solve_prepare, "lu_solve_prepare", lu, max_nrhs, workspace, stream)
+
+
+def cholesky_solve_prepare(l, max_nrhs: int, workspace=None, stream=None):
+    """The part of cholesky_solve that does not depend on the right-hand sides (see dla.h: cholesky_solve_prepare)."""
+    return _solve_prepare(lib.cholesky_solve_prepare, "cholesky_solve_prepare", l, max_nrhs, workspace, stream)
+
+
+def lu_solve_prepared(lu, b, workspace, stream=None):
+    """lu_solve with a workspace that lu_solve_prepare filled for this factor (see dla.h: lu_solve_prepared)."""
+    if workspace is None:
+        raise ValueError("lu_solve_prepared: pass the workspace lu_solve_prepare returned")
+    return _solve(lib.lu_solve_prepared, "lu_solve_prepared", lu, b, workspace, stream)
+
+
+def cholesky_solve_prepared(l, b, workspace, stream=None):
+    """cholesky_solve with a workspace that cholesky_solve_prepare filled for this factor."""
+    if workspace is None:
+        raise ValueError("cholesky_solve_prepared: pass the workspace cholesky_solve_prepare returned")
+    return _solve(lib.cholesky_solve_prepared, "cholesky_solve_prepared", l, b, workspace, stream)
 
 
 def mm3(a, b, c, d, g, p: Mm3Params | None = None, workspace=None, stream=None):

@@ -568,26 +568,63 @@ size_t solve_workspace_bytes(int64_t n, int64_t nrhs, dla_dtype dt) {
   return solve_workspace_bytes_impl(n, nrhs, dt);
 }
 
-int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
-             void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = solve_common_checks(d_lu, n, lda, d_b, nrhs, ldb, dt);
+extern "C++" {
+template <int KIND>
+static int solve_entry(const void* d_f, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+                       void* d_workspace, size_t workspace_bytes, void* hip_stream, int phases) {
+  int rc = solve_common_checks(d_f, n, lda, d_b, nrhs, ldb, dt);
   if (rc != DLA_SUCCESS) return rc;
   hip_clear_stale_error();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (dt == DLA_F64)
-    return solve_impl<double, 0>((const double*)d_lu, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
-  return solve_impl<float, 0>((const float*)d_lu, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
+    return solve_impl<double, KIND>((const double*)d_f, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st, phases);
+  return solve_impl<float, KIND>((const float*)d_f, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st, phases);
+}
+
+template <int KIND>
+static int solve_prepare_entry(const void* d_f, int64_t n, int64_t lda, dla_dtype dt, void* d_workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (n < 0) return -2;
+  if (dt != DLA_F64 && dt != DLA_F32) return -4;
+  if (n > 0 && (!d_f || ((uintptr_t)d_f % (size_t)esize(dt)))) return -1;
+  if (lda < (n > 0 ? n : 1)) return -3;
+  if (n > kMaxDim) return DLA_ERR_TOO_LARGE;
+  hip_clear_stale_error();
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (dt == DLA_F64)
+    return solve_impl<double, KIND>((const double*)d_f, n, lda, nullptr, 0, 1, d_workspace, workspace_bytes, st, kSolvePrepare);
+  return solve_impl<float, KIND>((const float*)d_f, n, lda, nullptr, 0, 1, d_workspace, workspace_bytes, st, kSolvePrepare);
+}
+}  // extern "C++"
+
+int lu_solve(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+             void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return solve_entry<0>(d_lu, n, lda, d_b, nrhs, ldb, dt, d_workspace, workspace_bytes, hip_stream, kSolvePrepare | kSolveApply);
 }
 
 int cholesky_solve(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = solve_common_checks(d_l, n, lda, d_b, nrhs, ldb, dt);
-  if (rc != DLA_SUCCESS) return rc;
-  hip_clear_stale_error();
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (dt == DLA_F64)
-    return solve_impl<double, 1>((const double*)d_l, n, lda, (double*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
-  return solve_impl<float, 1>((const float*)d_l, n, lda, (float*)d_b, nrhs, ldb, d_workspace, workspace_bytes, st);
+  return solve_entry<1>(d_l, n, lda, d_b, nrhs, ldb, dt, d_workspace, workspace_bytes, hip_stream, kSolvePrepare | kSolveApply);
+}
+
+int lu_solve_prepare(const void* d_lu, int64_t n, int64_t lda, dla_dtype dt, void* d_workspace, size_t workspace_bytes,
+                     void* hip_stream) {
+  return solve_prepare_entry<0>(d_lu, n, lda, dt, d_workspace, workspace_bytes, hip_stream);
+}
+
+int cholesky_solve_prepare(const void* d_l, int64_t n, int64_t lda, dla_dtype dt, void* d_workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  return solve_prepare_entry<1>(d_l, n, lda, dt, d_workspace, workspace_bytes, hip_stream);
+}
+
+int lu_solve_prepared(const void* d_lu, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+                      void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return solve_entry<0>(d_lu, n, lda, d_b, nrhs, ldb, dt, d_workspace, workspace_bytes, hip_stream, kSolveApply);
+}
+
+int cholesky_solve_prepared(const void* d_l, int64_t n, int64_t lda, void* d_b, int64_t nrhs, int64_t ldb, dla_dtype dt,
+                            void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return solve_entry<1>(d_l, n, lda, d_b, nrhs, ldb, dt, d_workspace, workspace_bytes, hip_stream, kSolveApply);
 }
 
 int dla_handover_selftest(void* d_scratch, size_t scratch_bytes, void* hip_stream, int* d_info) {

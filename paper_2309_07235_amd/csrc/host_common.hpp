@@ -74,10 +74,11 @@ int cholesky_factor_impl(T* A, int64_t n, int64_t lda, const dla_factor_params* 
 // The bulk trailing-update kernel on its own: C (m x m) -= L (m x b) * R (b x m), or lower(C) -= L * L^T.
 template <typename T>
 int rank_update_impl(bool lower, const T* L, const T* Rm, T* C, int64_t ld, int64_t m, int b, hipStream_t st);
-// Solve with the factors (solve.hip); KIND is FactorKind as an int.
+// Solve with the factors (solve.hip); KIND is FactorKind as an int; phases: which of its two parts to run.
+constexpr int kSolvePrepare = 1, kSolveApply = 2;
 template <typename T, int KIND>
 int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t ldb, void* ws, size_t ws_bytes,
-               hipStream_t st);
+               hipStream_t st, int phases);
 size_t solve_workspace_bytes_impl(int64_t n, int64_t nrhs, dla_dtype dt);
 size_t factor_workspace_bytes_impl(int64_t n, dla_dtype dt, const dla_factor_params* p);
 constexpr size_t kHandoverSelftestBytes = 8192;

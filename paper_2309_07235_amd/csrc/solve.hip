@@ -116,10 +116,13 @@ struct ProductList {
   }
 };
 
+// phases: kSolvePrepare = the pre-pass (independent of B; leaves the negated inverses and M in the workspace),
+// kSolveApply = the two passes over B with a workspace the pre-pass has filled for this factor; both = a whole solve.
 template <typename T, int KIND>
 int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t ldb, void* ws, size_t ws_bytes,
-               hipStream_t st) {
-  if (n == 0 || nrhs == 0) return DLA_SUCCESS;
+               hipStream_t st, int phases) {
+  const bool prepare = phases & kSolvePrepare, apply = (phases & kSolveApply) && nrhs > 0;
+  if (n == 0 || (nrhs == 0 && (phases & kSolveApply))) return DLA_SUCCESS;
   const dla_dtype dt = sizeof(T) == 8 ? DLA_F64 : DLA_F32;
   if (!ws || ws_bytes < solve_workspace_bytes_impl(n, nrhs, dt) || ((uintptr_t)ws % 256)) return DLA_ERR_WORKSPACE;
   constexpr int BOP = (KIND == KIND_LU) ? OP_SUB : OP_SUB_TN;  // the backward pass's one operation
@@ -143,10 +146,12 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
   const GemmSchedule sch = nrhs <= 256 ? small : GemmSchedule{64, 64, 16, 2, 32, 32};
   const GemmSchedule wide = GemmSchedule{64, 64, 16, 4, 32, 32};  // the 256 x 512 products of the pre-pass
   int rc;
-  // ---- pre-pass: every target of a subtracting product that stands for a plain one starts at zero
+  // ---- every target of a subtracting product that stands for a plain one starts at zero: the pre-pass's
+  // targets lie in front of Y, the passes' own (Y and X) behind them
   {
-    const int64_t count = block_elems(n) + 2 * n * ldy;
-    hipLaunchKernelGGL(solve_zero_kernel<T>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, wf, count);
+    T* const from = prepare ? wf : Y;
+    const int64_t count = (prepare ? block_elems(n) : 0) + (apply ? 2 * n * ldy : 0);
+    hipLaunchKernelGGL(solve_zero_kernel<T>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, from, count);
     if (launch_status(__func__) != DLA_SUCCESS) return DLA_ERR_HIP;
   }
   // with N = -W:  T = 0 - (off-diagonal block of the factor) * (N next to it) = block * W, then the
@@ -199,14 +204,17 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     }
     return r != DLA_SUCCESS ? r : list.flush(s);
   };
-  if (KIND == KIND_LU)
-    rc = launch_prepare_both<T, TRI_LOWER_UNIT, TRI_UPPER>(TriPrepareArgs<T>{F, lda, n, wf, T(-1)}, TriPrepareArgs<T>{F, lda, n, wb, T(-1)}, st);
-  else
-    rc = launch_prepare<T, TRI_LOWER>(TriPrepareArgs<T>{F, lda, n, wf, T(-1)}, st);
-  if (rc != DLA_SUCCESS) return rc;
-  if ((rc = pairing(0, st)) != DLA_SUCCESS) return rc;
-  if (KIND == KIND_LU && (rc = pairing(1, st)) != DLA_SUCCESS) return rc;
-  if ((rc = look_back(0, st)) != DLA_SUCCESS || (rc = look_back(1, st)) != DLA_SUCCESS) return rc;
+  if (prepare) {
+    if (KIND == KIND_LU)
+      rc = launch_prepare_both<T, TRI_LOWER_UNIT, TRI_UPPER>(TriPrepareArgs<T>{F, lda, n, wf, T(-1)}, TriPrepareArgs<T>{F, lda, n, wb, T(-1)}, st);
+    else
+      rc = launch_prepare<T, TRI_LOWER>(TriPrepareArgs<T>{F, lda, n, wf, T(-1)}, st);
+    if (rc != DLA_SUCCESS) return rc;
+    if ((rc = pairing(0, st)) != DLA_SUCCESS) return rc;
+    if (KIND == KIND_LU && (rc = pairing(1, st)) != DLA_SUCCESS) return rc;
+    if ((rc = look_back(0, st)) != DLA_SUCCESS || (rc = look_back(1, st)) != DLA_SUCCESS) return rc;
+  }
+  if (!apply) return DLA_SUCCESS;
   // ---- the chain: one grouped launch per block step
   struct Part {
     const T *a, *b;
@@ -310,9 +318,9 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
   return DLA_SUCCESS;
 }
 
-template int solve_impl<double, KIND_LU>(const double*, int64_t, int64_t, double*, int64_t, int64_t, void*, size_t, hipStream_t);
-template int solve_impl<float, KIND_LU>(const float*, int64_t, int64_t, float*, int64_t, int64_t, void*, size_t, hipStream_t);
-template int solve_impl<double, KIND_CHOL>(const double*, int64_t, int64_t, double*, int64_t, int64_t, void*, size_t, hipStream_t);
-template int solve_impl<float, KIND_CHOL>(const float*, int64_t, int64_t, float*, int64_t, int64_t, void*, size_t, hipStream_t);
+template int solve_impl<double, KIND_LU>(const double*, int64_t, int64_t, double*, int64_t, int64_t, void*, size_t, hipStream_t, int);
+template int solve_impl<float, KIND_LU>(const float*, int64_t, int64_t, float*, int64_t, int64_t, void*, size_t, hipStream_t, int);
+template int solve_impl<double, KIND_CHOL>(const double*, int64_t, int64_t, double*, int64_t, int64_t, void*, size_t, hipStream_t, int);
+template int solve_impl<float, KIND_CHOL>(const float*, int64_t, int64_t, float*, int64_t, int64_t, void*, size_t, hipStream_t, int);
 
 }  // namespace dla

@@ -169,6 +169,20 @@ def test_argument_errors_are_reported_without_gpu_work(B):
         assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, vp(0x1008), 1 << 20, None) == B.DLA_ERR_WORKSPACE
         assert solve(None, 0, 1, None, 2, 2, B.DLA_F64, None, 0, None) == 0  # nothing to solve
         assert solve(fake, 8, 8, None, 0, 1, B.DLA_F64, None, 0, None) == 0  # no right-hand side
+    for prep in (L.lu_solve_prepare, L.cholesky_solve_prepare):
+        assert prep(None, 8, 8, B.DLA_F64, fake, 1 << 22, None) == -1
+        assert prep(fake, -1, 8, B.DLA_F64, fake, 1 << 22, None) == -2
+        assert prep(fake, 8, 7, B.DLA_F64, fake, 1 << 22, None) == -3
+        assert prep(fake, 8, 8, 7, fake, 1 << 22, None) == -4
+        assert prep(fake, 8, 8, B.DLA_F64, None, 0, None) == B.DLA_ERR_WORKSPACE
+        assert prep(fake, 8, 8, B.DLA_F64, fake, L.solve_workspace_bytes(8, 0, B.DLA_F64) - 1, None) == B.DLA_ERR_WORKSPACE
+        assert prep(None, 0, 1, B.DLA_F64, None, 0, None) == 0  # nothing to prepare
+    for solve in (L.lu_solve_prepared, L.cholesky_solve_prepared):
+        assert solve(None, 8, 8, fake, 2, 2, B.DLA_F64, fake, 1 << 22, None) == -1
+        assert solve(fake, 8, 8, None, 2, 2, B.DLA_F64, fake, 1 << 22, None) == -4
+        assert solve(fake, 8, 8, fake, 3, 2, B.DLA_F64, fake, 1 << 22, None) == -6
+        assert solve(fake, 8, 8, fake, 2, 2, B.DLA_F64, fake, L.solve_workspace_bytes(8, 2, B.DLA_F64) - 1, None) == B.DLA_ERR_WORKSPACE
+        assert solve(fake, 8, 8, None, 0, 1, B.DLA_F64, None, 0, None) == 0  # no right-hand side
     # per 256-row block and pass: a 256 x 256 inverse, a 128 x 128 intermediate, a 256 x 512 look-back product; two n x nrhs areas
     assert L.solve_workspace_bytes(4000, 63, B.DLA_F64) == (2 * 16 * (256 * 256 + 128 * 128 + 256 * 512) + 2 * 4000 * 64) * 8
     assert L.solve_workspace_bytes(1, 1, B.DLA_F32) == (2 * (256 * 256 + 128 * 128 + 256 * 512) + 2 * 2) * 4

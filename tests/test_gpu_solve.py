@@ -55,6 +55,37 @@ def test_solve_matches_oracle(B, oracle, kind, n, nrhs):
 
 
 @pytest.mark.parametrize("kind", ["lu", "chol"])
+@pytest.mark.parametrize("n,dtype_name", [(700, "float64"), (129, "float64"), (1025, "float32")])
+def test_prepared_solves_equal_the_whole_solve(B, oracle, kind, n, dtype_name):
+    """One prepare call, then several solves of different widths with its workspace: each bit for bit what the
+    one-call solve gives (same kernels in the same order), and the first one checked against the oracle."""
+    import torch
+    dtype = getattr(torch, dtype_name)
+    announce(f"prepared solve {kind} n={n} {dtype_name}")
+    _, F = _factor(oracle, kind, n, 27)
+    if dtype_name == "float32":
+        F = F.astype(np.float32).astype(np.float64)
+    f = to_device(F, dtype)
+    whole = B.lu_solve if kind == "lu" else B.cholesky_solve
+    ws = (B.lu_solve_prepare if kind == "lu" else B.cholesky_solve_prepare)(f, 130)
+    prepared = B.lu_solve_prepared if kind == "lu" else B.cholesky_solve_prepared
+    for i, nrhs in enumerate((64, 5, 130, 33)):
+        rhs = inputs.uniform_matrix(28, i, n, nrhs)
+        if dtype_name == "float32":
+            rhs = rhs.astype(np.float32).astype(np.float64)
+        b1, b2 = to_device(rhs, dtype), to_device(rhs, dtype)
+        whole(f, b1)
+        prepared(f, b2, ws)
+        x1, x2 = to_host(b1), to_host(b2)
+        assert np.array_equal(x1, x2)
+        if i == 0:
+            want = (oracle.lu_solve if kind == "lu" else oracle.cholesky_solve)(F, rhs)
+            assert max_rel_err(x2.astype(np.float64), want) <= (TOL64 if dtype_name == "float64" else TOL32)
+    with pytest.raises(Exception):  # more right-hand sides than the workspace was sized for
+        prepared(f, to_device(inputs.uniform_matrix(28, 9, n, 200), dtype), ws)
+
+
+@pytest.mark.parametrize("kind", ["lu", "chol"])
 @pytest.mark.parametrize("n,nrhs", [(129, 3), (700, 40), (1025, 20)])
 def test_solve_fp32(B, oracle, kind, n, nrhs):
     import torch
