@@ -22,6 +22,8 @@
 // and the backward pass reads N, M^T and L's block rows as transposed left operands, so it needs no
 // inverses of its own.  The forward pass leaves Y in the workspace and spoils B; the backward pass
 // builds X in a second workspace area and stores each finished block to B as well.
+// The chain's launches run on skinny_kernel up to 128 right-hand sides and on the tiled GEMM above.
+// The pre-pass and the two passes can be called separately (one pre-pass, many solves with its workspace).
 #include "trisolve_kernel.hpp"
 #include "skinny_kernel.hpp"
 #include "host_common.hpp"
