@@ -143,9 +143,11 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
   auto rows_of = [&](int i) { return n - (int64_t)i * sb < sb ? n - (int64_t)i * sb : sb; };
   auto Nf = [&](int i) { return wf + (int64_t)i * sb * sb; };
   auto Nb = [&](int i) { return wb + (int64_t)i * sb * sb; };
-  // Above 128 right-hand sides the chain's launches run on the tiled GEMM: 32 x 32 tiles up to 256, 64 x 64 above.
+  // Where the chain's launches run on the tiled GEMM (many right-hand sides) they use its 32 x 32 tiles: the
+  // products stay skinny (k <= 512), and small tiles spread them over the compute units (N = 4000, 512
+  // right-hand sides: 0.87 ms against 1.22 ms with 64 x 64 tiles; N = 8192, 1024: 4.33 against 4.63 ms).
   const GemmSchedule small = GemmSchedule{32, 32, 16, 4, 16, 16};
-  const GemmSchedule sch = nrhs <= 256 ? small : GemmSchedule{64, 64, 16, 2, 32, 32};
+  const GemmSchedule sch = small;
   const GemmSchedule wide = GemmSchedule{64, 64, 16, 4, 32, 32};  // the 256 x 512 products of the pre-pass
   int rc;
   // ---- every target of a subtracting product that stands for a plain one starts at zero: the pre-pass's
@@ -224,11 +226,12 @@ int solve_impl(const T* F, int64_t n, int64_t lda, T* B, int64_t nrhs, int64_t l
     int64_t la, lb, lc, lc2, M, K;
     int many;  // 1 for product (c): many blocks, the factor as its left operand
   };
-  // Up to 128 right-hand sides a launch of the chain is a few hundred 16 x 16 blocks and what matters is how soon
-  // its longest product ends: the skinny kernel (one block per workgroup, k split over its waves; N = 4000, 64
-  // right-hand sides 0.39 ms against 0.48 ms on 32 x 32 tiles with 128-deep slabs, 0.61 ms with 16-deep ones);
-  // above that the tiled GEMM.
-  const bool skinny = nrhs <= 128;
+  // While a launch of the chain is a few hundred to a few thousand 16 x 16 blocks, what matters is how soon its
+  // longest product ends: the skinny kernel (one block per workgroup, k split over its waves; N = 4000, 64
+  // right-hand sides 0.37 ms against 0.48 ms on 32 x 32 tiles with 128-deep slabs, 0.61 ms with 16-deep ones;
+  // 256: 0.61 against 0.68 ms).  With more work per launch the tiled GEMM's reuse wins (N = 4000, 512: 0.98
+  // against 0.87 ms; N = 8192, 256: 1.99 against 1.89 ms).
+  const bool skinny = nrhs <= 128 || (nrhs <= 256 && n * nrhs <= 1200000);
   static_assert(2 * kTriPair <= kSkinnyMaxK, "the look-back product's depth");
   auto launch_parts = [&](int op, const Part* parts, int count) -> int {
     if (skinny) {
