@@ -271,7 +271,7 @@ constexpr int solve_lds_bytes() {
 template <typename T, int KIND>
 __global__ void __launch_bounds__(kSolveThreads) solve_kernel(const SolveArgs<T> g) {
   constexpr int NB = kNbMax / kIb;
-  constexpr int HALF = NB * (NB + 1) / 4;  // 18 of the 36 sub-blocks per staging pass
+  constexpr int NTRI = NB * (NB + 1) / 2;  // the 36 sub-blocks of the factor
   using acc_t = typename Mfma<T>::acc_t;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   T* const tri = reinterpret_cast<T*>(smem_raw);
@@ -312,34 +312,30 @@ __global__ void __launch_bounds__(kSolveThreads) solve_kernel(const SolveArgs<T>
     }
   }
 
-  // ---- stage the factor (two passes keep the staging registers few) -----------------------------
+  // ---- stage the factor: every load issued before the first LDS store (one round trip to memory; the
+  // staging registers are free, LDS already holds the workgroups of a compute unit to two) ---------
   {
     const int rr = tid >> 4, cc = tid & 15;
     const T* const inv = upper ? g.inv_up : g.inv_lo;
+    T v[NTRI];
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      T v[HALF];
+    for (int hi = 0; hi < NB; ++hi)
 #pragma unroll
-      for (int q = 0; q < HALF; ++q) {
-        const int tb = pass * HALF + q;
-        // tb -> (hi, lo), compile-time after unrolling
-        int hi = 0;
-        while ((hi + 1) * (hi + 2) / 2 <= tb) ++hi;
-        const int lo = tb - hi * (hi + 1) / 2;
-        if (hi < nblk) {
-          if (hi == lo) v[q] = inv[hi * 256 + rr * 16 + cc];
-          else if (upper) v[q] = g.D[(int64_t)(lo * kIb + rr) * lda + hi * kIb + cc];
-          else v[q] = g.D[(int64_t)(hi * kIb + rr) * lda + lo * kIb + cc];
+      for (int lo = 0; lo <= hi; ++lo) {
+        const int tb = hi * (hi + 1) / 2 + lo;
+        if (hi < nblk) {  // uniform
+          if (hi == lo) v[tb] = inv[hi * 256 + rr * 16 + cc];
+          else if (upper) v[tb] = g.D[(int64_t)(lo * kIb + rr) * lda + hi * kIb + cc];
+          else v[tb] = g.D[(int64_t)(hi * kIb + rr) * lda + lo * kIb + cc];
         }
       }
 #pragma unroll
-      for (int q = 0; q < HALF; ++q) {
-        const int tb = pass * HALF + q;
-        int hi = 0;
-        while ((hi + 1) * (hi + 2) / 2 <= tb) ++hi;
-        if (hi < nblk) tri[tb * kBlk + rr * (kIb + 1) + cc] = v[q];
+    for (int hi = 0; hi < NB; ++hi)
+#pragma unroll
+      for (int lo = 0; lo <= hi; ++lo) {
+        const int tb = hi * (hi + 1) / 2 + lo;
+        if (hi < nblk) tri[tb * kBlk + rr * (kIb + 1) + cc] = v[tb];
       }
-    }
   }
   __syncthreads();
   if (!job_on) return;
